@@ -1,0 +1,183 @@
+/*
+ * elasticmoe.h -- C ABI of the MI355X (gfx950) MoE expert layer as ONE
+ * expert-parallel rank runs it.
+ *
+ * What the layer is.  The paper (Sec. 2.1, "Distributed Inference for MoE
+ * Models") states the computation in one sentence: a layer holds many experts, a
+ * gating function selects a few of them per token, and under expert parallelism
+ * every device owns a subset of the experts to which tokens are routed.  This
+ * library runs that layer for the tokens and the experts of one rank:
+ *
+ *     gate logits -> scores -> top-k (optionally group limited) -> renormalise
+ *     -> logical expert id -> physical weight slot (expert map) -> rows grouped
+ *     per slot -> SwiGLU expert FFN per group -> weighted sum back per token.
+ *
+ * Why there is an expert map.  The paper's "Virtual Expert Management" design
+ * choice (Sec. 3.2) and its vpage-remap primitive (Sec. 4.6, App. D) keep the
+ * rank's expert weights in place when the expert-parallel degree changes: only a
+ * mapping is re-pointed, nothing large is reallocated or copied, and the old
+ * mapping stays usable until the switch.  Here the mapping is an int32 table
+ * `logical expert -> slot of a preallocated weight pool` that the kernels read;
+ * moe_set_expert_map swaps it in O(E) with no allocation and no weight traffic.
+ *
+ * Memory rules.  Every device buffer (weights, workspace, activations) is owned
+ * by the caller and must outlive the layer; the library never calls hipMalloc /
+ * hipFree.  This mirrors the paper's split between the memory daemon that owns
+ * tensors and the execution side that only holds references (Sec. 3.2,
+ * "Decoupled Memory and Execution Layers").  All pointers named "device" are
+ * device addresses valid on the GPU that is current when the call is made; all
+ * others are host addresses.  All calls are host-thread-safe only when they use
+ * different layers.
+ *
+ * Errors.  Every call returns a moe_status_t; nothing throws or aborts.  On any
+ * error the layer (including its active expert map) is unchanged and
+ * moe_last_error() describes the problem.
+ */
+#ifndef ELASTICMOE_H
+#define ELASTICMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_layer moe_layer_t; /* opaque host object */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_ARG = 1,         /* null pointer, negative size, bad enum, misaligned buffer */
+    MOE_ERR_SHAPE = 2,       /* sizes that do not describe a layer (E % n_group != 0, k > E, ...) */
+    MOE_ERR_MAP = 3,         /* invalid expert map, or forward before any map was set */
+    MOE_ERR_CAPACITY = 4,    /* T > max_tokens, workspace too small */
+    MOE_ERR_UNSUPPORTED = 5, /* a shape the kernels do not cover (see moe_layer_create) */
+    MOE_ERR_HIP = 6          /* a HIP runtime call failed (message has the HIP error string) */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+/*
+ * Gating rule (Sec. 2.1 names only "a gating function"; these are the rules of
+ * the model families the paper serves in Sec. 5).
+ *   MOE_GATE_SOFTMAX_TOPK        scores = softmax over all E logits; the k best.
+ *   MOE_GATE_SIGMOID_GROUP_TOPK  scores = sigmoid(logit); experts are split into
+ *       n_group equal consecutive groups; a group's score is the sum of its two
+ *       largest selection scores; only the topk_group best groups stay eligible;
+ *       the k best eligible experts are taken.
+ * Order is (score descending, lower index first) for experts and for groups.
+ * Weights are the un-biased scores of the k selected experts; if `renormalize`
+ * they are divided by their sum over all k (local or not); then multiplied by
+ * `routed_scale`.
+ */
+typedef enum { MOE_GATE_SOFTMAX_TOPK = 0, MOE_GATE_SIGMOID_GROUP_TOPK = 1 } moe_gate_t;
+
+typedef struct {
+    int32_t hidden;      /* H  : model width; multiple of 8 */
+    int32_t inter;       /* I  : SwiGLU intermediate width of one expert; multiple of 8 */
+    int32_t n_experts;   /* E  : logical (global) routed experts, 1..1024 */
+    int32_t top_k;       /* k  : 1..min(E,32) */
+    int32_t n_slots;     /* S  : physical weight slots in the caller's pool, shared included */
+    int32_t max_tokens;  /* largest T any moe_forward will pass */
+    int32_t act_dtype;   /* moe_dtype_t of x, w13, w2, out */
+    int32_t router_dtype;/* moe_dtype_t of router_w */
+    int32_t gate;        /* moe_gate_t */
+    int32_t n_group;     /* 1 unless MOE_GATE_SIGMOID_GROUP_TOPK; divides E; <= 64 */
+    int32_t topk_group;  /* 1..n_group; k <= topk_group * E / n_group */
+    int32_t renormalize; /* 0 / 1 */
+    float   routed_scale;/* e.g. 1.0 or 2.5 */
+    int32_t n_shared;    /* shared (always-on) experts living in the same slot pool, 0..4 */
+} moe_config_t;
+
+typedef struct {
+    const void  *router_w;    /* device [E,H] row-major, router_dtype */
+    const float *logit_bias;  /* device [E] fp32 or NULL; added to the logits before scoring */
+    const float *select_bias; /* device [E] fp32 or NULL; added to scores for SELECTION only */
+    const void  *w13;         /* device [S,2I,H] act_dtype: rows 0..I-1 gate proj, I..2I-1 up proj */
+    const void  *w2;          /* device [S,H,I]  act_dtype: down proj */
+    void        *workspace;   /* device, 256-byte aligned, >= moe_workspace_bytes(cfg) bytes */
+    size_t       workspace_bytes;
+} moe_buffers_t;
+
+/* device addresses of the intermediates inside the caller's workspace (for tests) */
+typedef struct {
+    const int32_t *topk_ids;  /* [T,k]    logical expert ids, best first */
+    const float   *topk_w;    /* [T,k]    combine weights of those experts */
+    const int32_t *counts;    /* [S]      rows per slot in the last forward */
+    const int32_t *offsets;   /* [S+1]    exclusive prefix sum of counts */
+    const int32_t *perm;      /* [A]      token index of every grouped row, A = offsets[S] */
+    const int32_t *inv;       /* [T,k+n_shared] grouped row of every assignment or -1 */
+    const void    *h;         /* [A,I]    act_dtype, silu(gate)*up */
+    const void    *y;         /* [A,H]    act_dtype, expert outputs before combine */
+    const int32_t *active_map;/* [E + n_shared] the device copy of the active map, shared slots last */
+} moe_workspace_view_t;
+
+/* moe_forward flags */
+#define MOE_FLAG_IDENTITY_EXPERTS 1u /* test mode: every expert returns its input row unchanged */
+#define MOE_FLAG_FORCE_GENERIC    2u /* run the plain (non-MFMA) expert kernels: debugging aid */
+
+/*
+ * Bytes of device workspace a layer of this configuration needs (0 if cfg is
+ * invalid; moe_last_error() says why).  Pure host arithmetic.
+ */
+size_t moe_workspace_bytes(const moe_config_t *cfg);
+
+/*
+ * Create a layer object over caller-owned buffers.  Host-only: validates the
+ * configuration and the buffer pointers/alignment (router_w, w13, w2 16-byte,
+ * workspace 256-byte aligned), carves the workspace, touches no device memory
+ * and launches nothing.  The layer has NO expert map yet.
+ *   MOE_ERR_UNSUPPORTED: H or I not a multiple of 8, E > 1024, k > 32,
+ *   n_group > 64, n_shared > 4.
+ */
+moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf, moe_layer_t **out);
+
+/*
+ * Install a new expert placement (paper: vpage-remap, Sec. 4.6 / App. D; scale-up
+ * step "HMM Reconfigures Memory Layout", Sec. 4.7).
+ *   host_map [n]           n must equal E; entry e is the slot holding logical expert e,
+ *                          or -1 when the expert lives on another rank.
+ *   host_shared_slots [n_shared]  slots of the shared experts (NULL iff n_shared == 0).
+ * Rejected with MOE_ERR_MAP, leaving the old map active: n != E, an entry < -1 or
+ * >= S, two experts (or an expert and a shared expert) on one slot.
+ * The table is copied out of the host arrays before the call returns.  The device
+ * copy is written by a tiny kernel enqueued on `hip_stream` into the INACTIVE one
+ * of two device tables; forwards enqueued earlier keep reading the old table, and
+ * forwards issued after this call read the new one.  No allocation, no
+ * synchronisation, no weight traffic.  The caller must have filled the newly
+ * referenced weight slots (stream-ordered before the next forward).
+ */
+moe_status_t moe_set_expert_map(moe_layer_t *layer, const int32_t *host_map, int32_t n,
+                                const int32_t *host_shared_slots, void *hip_stream);
+
+/*
+ * One forward pass of the layer, enqueued on `hip_stream` (a hipStream_t; NULL =
+ * the default stream).  Asynchronous, never synchronises, never allocates.
+ *   x    device [T,H] act_dtype, 16-byte aligned
+ *   out  device [T,H] act_dtype, 16-byte aligned; row t = sum over the token's
+ *        LOCAL selected experts of weight * FFN_slot(x_t), plus 1.0 * FFN(x_t)
+ *        of every shared expert when shared_begin <= t < shared_end; a token with
+ *        no local work gets an all-zero row (a partial sum for the cross-rank
+ *        reduction).  The sum runs in selection order, shared experts last, in
+ *        fp32 with one final rounding.
+ *   T == 0 is a no-op.  T > max_tokens -> MOE_ERR_CAPACITY.
+ *   shared range must satisfy 0 <= shared_begin <= shared_end <= T.
+ * After the pass the workspace holds the intermediates moe_workspace_view names.
+ */
+moe_status_t moe_forward(moe_layer_t *layer, const void *x, int32_t T,
+                         int32_t shared_begin, int32_t shared_end,
+                         void *out, void *hip_stream, uint32_t flags);
+
+/* Addresses of the intermediates (valid for the layer's lifetime). */
+moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *view);
+
+/* Frees the host object only (the library owns no device memory). NULL is allowed. */
+void moe_layer_destroy(moe_layer_t *layer);
+
+/* Message of the last failing call on this host thread ("" if none). */
+const char *moe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELASTICMOE_H */

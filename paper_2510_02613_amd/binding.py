@@ -1,0 +1,137 @@
+"""ctypes binding of libelasticmoe.so: the same entry points, argument
+marshalling only.  Every step of the layer runs in the HIP kernels; this module
+holds no arithmetic and has no fallback: if the library is missing or a call
+fails it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libelasticmoe.so")
+
+MOE_OK, MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_MAP, MOE_ERR_CAPACITY, MOE_ERR_UNSUPPORTED, MOE_ERR_HIP = range(7)
+MOE_F32, MOE_BF16 = 0, 1
+MOE_GATE_SOFTMAX_TOPK, MOE_GATE_SIGMOID_GROUP_TOPK = 0, 1
+MOE_FLAG_IDENTITY_EXPERTS, MOE_FLAG_FORCE_GENERIC = 1, 2
+
+STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_MAP",
+                4: "MOE_ERR_CAPACITY", 5: "MOE_ERR_UNSUPPORTED", 6: "MOE_ERR_HIP"}
+
+# every symbol include/elasticmoe.h declares
+EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
+           "moe_workspace_view", "moe_layer_destroy", "moe_last_error")
+
+
+class MoEConfig(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int32), ("inter", ctypes.c_int32), ("n_experts", ctypes.c_int32),
+                ("top_k", ctypes.c_int32), ("n_slots", ctypes.c_int32), ("max_tokens", ctypes.c_int32),
+                ("act_dtype", ctypes.c_int32), ("router_dtype", ctypes.c_int32), ("gate", ctypes.c_int32),
+                ("n_group", ctypes.c_int32), ("topk_group", ctypes.c_int32), ("renormalize", ctypes.c_int32),
+                ("routed_scale", ctypes.c_float), ("n_shared", ctypes.c_int32)]
+
+
+class MoEBuffers(ctypes.Structure):
+    _fields_ = [("router_w", ctypes.c_void_p), ("logit_bias", ctypes.c_void_p),
+                ("select_bias", ctypes.c_void_p), ("w13", ctypes.c_void_p), ("w2", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class MoEWorkspaceView(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("topk_ids", "topk_w", "counts", "offsets", "perm", "inv", "h", "y", "active_map")]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libelasticmoe.so (built in-tree by paper_2510_02613_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2510_02613_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.moe_workspace_bytes.restype = ctypes.c_size_t
+        L.moe_workspace_bytes.argtypes = [ctypes.POINTER(MoEConfig)]
+        L.moe_layer_create.restype = ctypes.c_int
+        L.moe_layer_create.argtypes = [ctypes.POINTER(MoEConfig), ctypes.POINTER(MoEBuffers),
+                                       ctypes.POINTER(ctypes.c_void_p)]
+        L.moe_set_expert_map.restype = ctypes.c_int
+        L.moe_set_expert_map.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+                                         ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+        L.moe_forward.restype = ctypes.c_int
+        L.moe_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32]
+        L.moe_workspace_view.restype = ctypes.c_int
+        L.moe_workspace_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(MoEWorkspaceView)]
+        L.moe_layer_destroy.restype = None
+        L.moe_layer_destroy.argtypes = [ctypes.c_void_p]
+        L.moe_last_error.restype = ctypes.c_char_p
+        L.moe_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def moe_last_error() -> str:
+    return lib().moe_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != MOE_OK:
+        raise MoEError(status, moe_last_error())
+
+
+def moe_workspace_bytes(cfg: MoEConfig) -> int:
+    n = lib().moe_workspace_bytes(ctypes.byref(cfg))
+    if n == 0:
+        raise MoEError(MOE_ERR_SHAPE, moe_last_error())
+    return int(n)
+
+
+def moe_layer_create(cfg: MoEConfig, buf: MoEBuffers) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    _check(lib().moe_layer_create(ctypes.byref(cfg), ctypes.byref(buf), ctypes.byref(h)))
+    return h
+
+
+def _i32_array(vals: Optional[Sequence[int]]):
+    if vals is None:
+        return None, 0
+    vals = [int(v) for v in vals]
+    return (ctypes.c_int32 * len(vals))(*vals), len(vals)
+
+
+def moe_set_expert_map(layer, host_map: Sequence[int], host_shared_slots: Optional[Sequence[int]] = None,
+                       stream: int = 0) -> None:
+    m, n = _i32_array(host_map)
+    s, ns = _i32_array(host_shared_slots)
+    if ns == 0:
+        s = None
+    _check(lib().moe_set_expert_map(layer, m, n, s, ctypes.c_void_p(stream)))
+
+
+def moe_forward(layer, x_ptr: int, T: int, out_ptr: int, shared_begin: int = 0, shared_end: int = 0,
+                stream: int = 0, flags: int = 0) -> None:
+    _check(lib().moe_forward(layer, ctypes.c_void_p(x_ptr), T, shared_begin, shared_end,
+                             ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream), flags))
+
+
+def moe_workspace_view(layer) -> MoEWorkspaceView:
+    v = MoEWorkspaceView()
+    _check(lib().moe_workspace_view(layer, ctypes.byref(v)))
+    return v
+
+
+def moe_layer_destroy(layer) -> None:
+    lib().moe_layer_destroy(layer)

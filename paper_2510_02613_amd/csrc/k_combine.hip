@@ -1,0 +1,94 @@
+// Un-permute and weighted combine: out[t] = sum_j w[t,j] * y[inv[t,j]].
+//
+// The sum runs over the token's assignments in selection order (routed experts
+// first, then the shared experts with weight 1), skipping experts that live on
+// another rank (inv == -1); accumulation is fp32 with a single final rounding, so
+// the result does not depend on which physical slot an expert occupies -- the
+// property the paper's remapping needs (Sec. 3.2, "Virtual Expert Management":
+// kernels see the same logical layout whatever the physical placement).
+// A token with no local assignment gets a zero row (partial sum for the
+// cross-rank reduction of expert parallelism, Sec. 2.1).
+//
+// One workgroup per token; each lane owns 16-byte column chunks so that every y
+// row and the out row are read / written fully coalesced.
+#include "moe_internal.h"
+
+namespace emoe {
+namespace {
+
+constexpr int kMaxKK = 36;  // top_k <= 32 plus <= 4 shared experts
+
+template <typename T> struct Chunk;
+template <> struct Chunk<uint16_t> { static constexpr int n = 8; };  // 8 bf16 = 16 B
+template <> struct Chunk<float> { static constexpr int n = 4; };     // 4 fp32 = 16 B
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_combine(Pass p)
+{
+    constexpr int C = Chunk<T>::n;
+    __shared__ int32_t rows[kMaxKK];
+    __shared__ float wts[kMaxKK];
+    const int t = blockIdx.x;
+    if (threadIdx.x < p.kk) {
+        const int j = threadIdx.x;
+        rows[j] = p.inv[(size_t)t * p.kk + j];
+        wts[j] = j < p.k ? p.w[(size_t)t * p.k + j] : 1.0f;
+    }
+    __syncthreads();
+    const T *y = (const T *)p.y;
+    T *out = (T *)p.out + (size_t)t * p.H;
+    for (int c = threadIdx.x * C; c < p.H; c += 256 * C) {
+        float acc[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) acc[i] = 0.f;
+        for (int j = 0; j < p.kk; ++j) {
+            const int r = rows[j];
+            if (r < 0) continue;
+            const float wj = wts[j];
+            const uint4 raw = *(const uint4 *)(y + (size_t)r * p.H + c);
+            const T *v = (const T *)&raw;
+#pragma unroll
+            for (int i = 0; i < C; ++i) acc[i] = fmaf(wj, load_f32<T>(v, i), acc[i]);
+        }
+        uint4 o;
+        T *ov = (T *)&o;
+#pragma unroll
+        for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[i]);
+        *(uint4 *)(out + c) = o;
+    }
+}
+
+struct MapChunk { int32_t v[256]; };
+
+__global__ void k_write_map(int32_t *dst, MapChunk c, int n)
+{
+    const int i = threadIdx.x;
+    if (i < n) dst[i] = c.v[i];
+}
+
+}  // namespace
+
+hipError_t launch_combine(const Pass &p, hipStream_t st)
+{
+    if (p.act_bf16) hipLaunchKernelGGL((k_combine<uint16_t>), dim3(p.T), dim3(256), 0, st, p);
+    else            hipLaunchKernelGGL((k_combine<float>), dim3(p.T), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+// The table travels as a kernel argument (captured at launch time), so the host
+// array may be reused as soon as this returns and the write is ordered on `st`
+// like any other kernel; no staging buffer, no memcpy node.
+hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st)
+{
+    for (int o = 0; o < n; o += 256) {
+        MapChunk c;
+        const int m = n - o < 256 ? n - o : 256;
+        for (int i = 0; i < 256; ++i) c.v[i] = i < m ? host_vals[o + i] : -1;
+        hipLaunchKernelGGL(k_write_map, dim3(1), dim3(256), 0, st, dst + o, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace emoe

@@ -1,0 +1,223 @@
+// Gating: logits, scores, (group limited) top-k, renormalised weights.
+//
+// The paper (Sec. 2.1) only says that a gating function picks a few experts per
+// token; the rules implemented here are the two its evaluated model families use:
+// softmax over all experts then top-k, and sigmoid scores with group-limited
+// top-k (group score = sum of the group's two best), both with optional
+// renormalisation over the k selected and a constant scale.
+//
+// One workgroup owns kTokens tokens.  Phase 1 accumulates their logits in fp32
+// (activations and router rows staged through LDS in K-chunks).  Phase 2 gives
+// each token to one 64-lane wavefront: scores live in LDS, every arg-max is a
+// wavefront reduction over a 64-bit (score, inverted index) key, so ties go to
+// the lower index exactly as the ordering rule demands.
+#include "moe_internal.h"
+
+namespace emoe {
+
+namespace {
+
+constexpr int kTokens = 8;     // tokens per workgroup
+constexpr int kThreads = 256;  // 4 wavefronts
+constexpr int kET = 128;       // experts per logit tile
+constexpr int kKC = 32;        // K chunk
+
+// Monotone map float -> uint32 (larger float <-> larger integer).
+__device__ __forceinline__ uint32_t orderable(float f)
+{
+    uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// key: larger = better score, and among equal scores the LOWER index
+__device__ __forceinline__ unsigned long long make_key(float score, int idx)
+{
+    return ((unsigned long long)orderable(score) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)idx);
+}
+__device__ __forceinline__ int key_index(unsigned long long key) { return (int)(0xffffffffu - (uint32_t)(key & 0xffffffffull)); }
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        unsigned long long o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+// Orders this wavefront's LDS traffic: writes before it are visible to every lane after it.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Phase 2 for one token, run by one wavefront.
+//   lg   : LDS [E] logits in, scores out
+//   cs   : LDS [E] selection scores (biased), destroyed (taken entries -> -inf)
+//   gsc  : LDS [n_group] group scores
+__device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *gsc, int lane)
+{
+    const int E = p.E;
+    const float NEG = -__builtin_huge_valf();
+    // scores
+    if (p.gate == MOE_GATE_SOFTMAX_TOPK) {
+        float m = NEG;
+        for (int e = lane; e < E; e += 64) m = fmaxf(m, lg[e]);
+        m = wave_max_f32(m);
+        float z = 0.f;
+        for (int e = lane; e < E; e += 64) { float v = expf(lg[e] - m); lg[e] = v; z += v; }
+        z = wave_sum_f32(z);
+        for (int e = lane; e < E; e += 64) lg[e] = lg[e] / z;
+    } else {
+        for (int e = lane; e < E; e += 64) lg[e] = 1.f / (1.f + expf(-lg[e]));
+    }
+    for (int e = lane; e < E; e += 64) cs[e] = lg[e] + (p.select_bias ? p.select_bias[e] : 0.f);
+    wave_sync();
+    // group limiting
+    if (p.gate == MOE_GATE_SIGMOID_GROUP_TOPK && p.n_group > 1) {
+        const int G = p.n_group, per = E / G;
+        float gs = NEG;
+        if (lane < G) {
+            float b1 = NEG, b2 = NEG;
+            for (int e = lane * per; e < (lane + 1) * per; ++e) {
+                float v = cs[e];
+                if (v > b1) { b2 = b1; b1 = v; } else if (v > b2) { b2 = v; }
+            }
+            gs = (per > 1) ? b1 + b2 : b1;
+        }
+        // pick topk_group groups; lane g remembers whether its group was kept
+        bool kept = false;
+        for (int r = 0; r < p.topk_group; ++r) {
+            unsigned long long key = (lane < G && !kept) ? make_key(gs, lane) : 0ull;
+            int win = key_index(wave_max_u64(key));
+            if (lane == win) kept = true;
+        }
+        if (lane < G) gsc[lane] = kept ? 1.f : 0.f;
+        wave_sync();
+        for (int e = lane; e < E; e += 64)
+            if (gsc[e / per] == 0.f) cs[e] = NEG;
+        wave_sync();
+    }
+    // top-k by repeated wavefront arg-max
+    int my_id = 0;
+    float my_s = 0.f;
+    for (int j = 0; j < p.k; ++j) {
+        unsigned long long key = 0ull;
+        for (int e = lane; e < E; e += 64) {
+            float v = cs[e];
+            if (v != NEG) { unsigned long long kk = make_key(v, e); key = kk > key ? kk : key; }
+        }
+        key = wave_max_u64(key);
+        int win = key_index(key);
+        if (lane == j) { my_id = win; my_s = lg[win]; }
+        if (lane == (win & 63)) cs[win] = NEG;
+        wave_sync();
+    }
+    float sum = wave_sum_f32(lane < p.k ? my_s : 0.f);
+    if (lane < p.k) {
+        float wv = p.renormalize ? my_s / sum : my_s;
+        p.ids[(size_t)t * p.k + lane] = my_id;
+        p.w[(size_t)t * p.k + lane] = wv * p.routed_scale;
+    }
+}
+
+template <typename XT, typename WT>
+__global__ __launch_bounds__(kThreads) void k_gate(Pass p)
+{
+    extern __shared__ float smem[];
+    float *xs = smem;                        // [kTokens][kKC]
+    float *ws = xs + kTokens * kKC;          // [kET][kKC+1]
+    float *lg = ws + kET * (kKC + 1);        // [kTokens][E]
+    float *cs = lg + kTokens * p.E;          // [4 waves][E]
+    float *gsc = cs + 4 * p.E;               // [4 waves][64]
+
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * kTokens;
+    const XT *x = (const XT *)p.x;
+    const WT *wr = (const WT *)p.router_w;
+    const int H = p.H, E = p.E;
+
+    // phase 1: logits.  thread -> expert (tid % 128) of the tile, tokens (tid / 128) * 4 .. +4
+    const int el = tid & (kET - 1);
+    const int th = (tid >> 7) * (kTokens / 2);
+    for (int e0 = 0; e0 < E; e0 += kET) {
+        float acc[kTokens / 2];
+#pragma unroll
+        for (int i = 0; i < kTokens / 2; ++i) acc[i] = 0.f;
+        for (int k0 = 0; k0 < H; k0 += kKC) {
+            __syncthreads();
+            {   // stage x chunk: kTokens*kKC = 256 values, one per thread
+                int tt = tid / kKC, kc = tid % kKC;
+                int t = t0 + tt, kx = k0 + kc;
+                xs[tt * kKC + kc] = (t < p.T && kx < H) ? load_f32<XT>(x, (size_t)t * H + kx) : 0.f;
+            }
+            for (int idx = tid; idx < kET * kKC; idx += kThreads) {
+                int er = idx / kKC, kc = idx % kKC;
+                int e = e0 + er, kx = k0 + kc;
+                ws[er * (kKC + 1) + kc] = (e < E && kx < H) ? load_f32<WT>(wr, (size_t)e * H + kx) : 0.f;
+            }
+            __syncthreads();
+#pragma unroll 8
+            for (int kc = 0; kc < kKC; ++kc) {
+                float wv = ws[el * (kKC + 1) + kc];
+#pragma unroll
+                for (int i = 0; i < kTokens / 2; ++i) acc[i] = fmaf(xs[(th + i) * kKC + kc], wv, acc[i]);
+            }
+        }
+        int e = e0 + el;
+        if (e < E) {
+            float b = p.logit_bias ? p.logit_bias[e] : 0.f;
+#pragma unroll
+            for (int i = 0; i < kTokens / 2; ++i) lg[(th + i) * E + e] = acc[i] + b;
+        }
+    }
+    __syncthreads();
+
+    // phase 2: one wavefront per token
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int tt = wave; tt < kTokens; tt += 4) {
+        int t = t0 + tt;
+        if (t < p.T) select_token(p, t, lg + tt * E, cs + wave * E, gsc + wave * 64, lane);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gate(const Pass &p, hipStream_t st)
+{
+    const int blocks = (p.T + kTokens - 1) / kTokens;
+    const size_t smem = sizeof(float) * (kTokens * kKC + kET * (kKC + 1) + (size_t)kTokens * p.E + 4 * (size_t)p.E + 4 * 64);
+    dim3 grid(blocks), block(kThreads);
+    if (smem > 64 * 1024) {  // opt in to the large-LDS launch once per kernel variant is cheap enough
+        hipError_t e = hipSuccess;
+        if (p.act_bf16 && p.router_bf16) e = hipFuncSetAttribute((const void *)k_gate<uint16_t, uint16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        else if (p.act_bf16)             e = hipFuncSetAttribute((const void *)k_gate<uint16_t, float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        else if (p.router_bf16)          e = hipFuncSetAttribute((const void *)k_gate<float, uint16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        else                             e = hipFuncSetAttribute((const void *)k_gate<float, float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    if (p.act_bf16) {
+        if (p.router_bf16) hipLaunchKernelGGL((k_gate<uint16_t, uint16_t>), grid, block, smem, st, p);
+        else               hipLaunchKernelGGL((k_gate<uint16_t, float>), grid, block, smem, st, p);
+    } else {
+        if (p.router_bf16) hipLaunchKernelGGL((k_gate<float, uint16_t>), grid, block, smem, st, p);
+        else               hipLaunchKernelGGL((k_gate<float, float>), grid, block, smem, st, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace emoe

@@ -1,0 +1,157 @@
+// Routing bookkeeping between the gate and the expert GEMMs.
+//
+// Every (token, selected expert) pair whose expert is resident on this rank
+// becomes one row of a slot-grouped activation matrix.  "Resident" is decided by
+// the expert map: the paper's virtual expert management (Sec. 3.2; vpage-remap,
+// Sec. 4.6 / App. D) lets the expert placement change without moving weights, so
+// the kernels here translate logical expert ids to physical weight slots on every
+// pass and never assume a placement.
+//
+//   k_slot_hist  per block of 256 assignments: slot lookup, LDS histogram, and the
+//                rank of every assignment among the block's earlier assignments to
+//                the same slot (deterministic: token order).
+//   k_slot_scan  one block: per-slot running sum over the blocks, exclusive prefix
+//                sum over slots (LDS scan), and the M-tile list for the GEMMs.
+//   k_slot_place row = offsets[slot] + block base + rank; perm[row] = token,
+//                inv[assignment] = row (or -1 when the expert is not local).
+//
+// Rows of one slot end up ordered by (token, selection position); nothing depends
+// on atomics ordering, so two passes over the same input give the same layout.
+#include "moe_internal.h"
+
+namespace emoe {
+namespace {
+
+constexpr int kThreads = kAssignPerBlock;
+
+__global__ __launch_bounds__(kThreads) void k_slot_hist(Pass p)
+{
+    extern __shared__ int32_t sm[];
+    int32_t *hist = sm;          // [S]
+    int32_t *slots = sm + p.S;   // [kThreads]
+    const int tid = threadIdx.x;
+    for (int s = tid; s < p.S; s += kThreads) hist[s] = 0;
+    const int a = blockIdx.x * kThreads + tid;
+    const int n_assign = p.T * p.kk;
+    int slot = -1;
+    if (a < n_assign) {
+        const int t = a / p.kk, j = a - t * p.kk;
+        if (j < p.k) {
+            slot = p.map[p.ids[(size_t)t * p.k + j]];
+        } else if (t >= p.shared_begin && t < p.shared_end) {
+            slot = p.map[p.E + (j - p.k)];
+        }
+    }
+    slots[tid] = slot;
+    __syncthreads();
+    if (slot >= 0) atomicAdd(&hist[slot], 1);
+    int rank = 0;
+    if (slot >= 0)
+        for (int i = 0; i < tid; ++i) rank += (slots[i] == slot);
+    if (a < n_assign) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
+    __syncthreads();
+    for (int s = tid; s < p.S; s += kThreads) p.blk_hist[(size_t)blockIdx.x * p.S + s] = hist[s];
+}
+
+// exclusive scan of v over the 256 threads of the block (v is per-thread), returns the
+// exclusive prefix; *total receives the block sum.  scratch: 8 ints of LDS.
+__device__ __forceinline__ int block_exclusive_scan(int v, int32_t *scratch, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) scratch[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        int s = scratch[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+__global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, int tile_rows)
+{
+    __shared__ int32_t scratch[8];
+    const int tid = threadIdx.x;
+    const int S = p.S;
+    // 1. per slot: running sum over blocks (blk_hist becomes the block's exclusive base)
+    for (int s = tid; s < S; s += kThreads) {
+        int run = 0;
+#pragma unroll 4
+        for (int b = 0; b < n_blocks; ++b) {
+            int32_t *q = p.blk_hist + (size_t)b * S + s;
+            int c = *q;
+            *q = run;
+            run += c;
+        }
+        p.counts[s] = run;
+    }
+    __syncthreads();
+    // 2. exclusive scans over slots, in chunks of 256 slots: row offsets and tile offsets
+    int row_carry = 0, tile_carry = 0;
+    for (int s0 = 0; s0 < S; s0 += kThreads) {
+        const int s = s0 + tid;
+        const int c = s < S ? p.counts[s] : 0;
+        const int nt = (c + tile_rows - 1) / tile_rows;
+        int row_tot, tile_tot;
+        const int row_off = row_carry + block_exclusive_scan(c, scratch, &row_tot);
+        const int tile_off = tile_carry + block_exclusive_scan(nt, scratch, &tile_tot);
+        if (s < S) {
+            p.offs[s] = row_off;
+            for (int i = 0; i < nt; ++i) {
+                const int idx = tile_off + i;
+                if (idx < p.max_tiles) {
+                    MTile mt;
+                    mt.slot = s;
+                    mt.row_begin = row_off + i * tile_rows;
+                    mt.rows = min(tile_rows, c - i * tile_rows);
+                    mt.pad = 0;
+                    p.tiles[idx] = mt;
+                }
+            }
+        }
+        row_carry += row_tot;
+        tile_carry += tile_tot;
+    }
+    if (tid == 0) {
+        p.offs[S] = row_carry;
+        *p.n_tiles = min(tile_carry, p.max_tiles);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
+{
+    const int a = blockIdx.x * kThreads + threadIdx.x;
+    if (a >= p.T * p.kk) return;
+    const int sr = p.slot_rank[a];
+    int row = -1;
+    if (sr >= 0) {
+        const int slot = sr >> 12, rank = sr & 0xfff;
+        row = p.offs[slot] + p.blk_hist[(size_t)blockIdx.x * p.S + slot] + rank;
+        p.perm[row] = a / p.kk;
+    }
+    p.inv[a] = row;
+}
+
+}  // namespace
+
+hipError_t launch_permute(const Pass &p, int tile_rows, hipStream_t st)
+{
+    const int n_assign = p.T * p.kk;
+    const int nb = (n_assign + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kThreads), sizeof(int32_t) * (p.S + kThreads), st, p);
+    hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows);
+    hipLaunchKernelGGL(k_slot_place, dim3(nb), dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace emoe

@@ -1,0 +1,256 @@
+// Host side of libelasticmoe.so: argument checking, workspace carving, the
+// expert-map switch and the launch sequence of one forward pass.
+//
+// The library owns no device memory (the paper's execution processes only hold
+// references to tensors kept by the memory daemon, Sec. 3.2 "Decoupled Memory and
+// Execution Layers"); all intermediates live in the caller's workspace, which is
+// carved once at create time, so no later call can allocate.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "moe_internal.h"
+
+using namespace emoe;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+moe_status_t fail(moe_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: sizes the tile list
+
+// Offsets of every intermediate inside the workspace.
+struct Layout {
+    size_t map[2], ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, total;
+};
+
+size_t esize(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+moe_status_t check_config(const moe_config_t *c)
+{
+    if (!c) return fail(MOE_ERR_ARG, "config is NULL");
+    if (c->hidden <= 0 || c->inter <= 0 || c->n_experts <= 0 || c->top_k <= 0 || c->n_slots <= 0 || c->max_tokens <= 0)
+        return fail(MOE_ERR_SHAPE, "hidden, inter, n_experts, top_k, n_slots, max_tokens must all be positive");
+    if (c->act_dtype != MOE_F32 && c->act_dtype != MOE_BF16) return fail(MOE_ERR_ARG, "act_dtype %d is not a moe_dtype_t", c->act_dtype);
+    if (c->router_dtype != MOE_F32 && c->router_dtype != MOE_BF16) return fail(MOE_ERR_ARG, "router_dtype %d is not a moe_dtype_t", c->router_dtype);
+    if (c->gate != MOE_GATE_SOFTMAX_TOPK && c->gate != MOE_GATE_SIGMOID_GROUP_TOPK) return fail(MOE_ERR_ARG, "gate %d is not a moe_gate_t", c->gate);
+    if (c->n_shared < 0 || c->n_group <= 0 || c->topk_group <= 0) return fail(MOE_ERR_SHAPE, "n_shared >= 0, n_group >= 1, topk_group >= 1 required");
+    if (c->top_k > c->n_experts) return fail(MOE_ERR_SHAPE, "top_k %d exceeds n_experts %d", c->top_k, c->n_experts);
+    if (c->n_experts % c->n_group) return fail(MOE_ERR_SHAPE, "n_group %d does not divide n_experts %d", c->n_group, c->n_experts);
+    if (c->topk_group > c->n_group) return fail(MOE_ERR_SHAPE, "topk_group %d exceeds n_group %d", c->topk_group, c->n_group);
+    if (c->gate == MOE_GATE_SOFTMAX_TOPK && (c->n_group != 1 || c->topk_group != 1))
+        return fail(MOE_ERR_SHAPE, "the softmax gate has no groups: n_group and topk_group must be 1");
+    if ((long long)c->top_k > (long long)c->topk_group * (c->n_experts / c->n_group))
+        return fail(MOE_ERR_SHAPE, "top_k %d exceeds the %d experts of %d kept groups", c->top_k, c->topk_group * (c->n_experts / c->n_group), c->topk_group);
+    if (c->n_shared > c->n_slots) return fail(MOE_ERR_SHAPE, "n_shared %d exceeds n_slots %d", c->n_shared, c->n_slots);
+    if (!(c->routed_scale == c->routed_scale)) return fail(MOE_ERR_ARG, "routed_scale is NaN");
+    if (c->hidden % 8 || c->inter % 8) return fail(MOE_ERR_UNSUPPORTED, "hidden and inter must be multiples of 8 (16-byte rows)");
+    if (c->n_experts > 1024) return fail(MOE_ERR_UNSUPPORTED, "n_experts > 1024");
+    if (c->top_k > 32) return fail(MOE_ERR_UNSUPPORTED, "top_k > 32");
+    if (c->n_group > 64) return fail(MOE_ERR_UNSUPPORTED, "n_group > 64");
+    if (c->n_shared > 4) return fail(MOE_ERR_UNSUPPORTED, "n_shared > 4");
+    if (c->n_slots > 2047) return fail(MOE_ERR_UNSUPPORTED, "n_slots > 2047");
+    if ((long long)c->max_tokens * (c->top_k + c->n_shared) > (1ll << 26))
+        return fail(MOE_ERR_UNSUPPORTED, "max_tokens * (top_k + n_shared) > 2^26");
+    return MOE_OK;
+}
+
+Layout make_layout(const moe_config_t &c)
+{
+    Layout L;
+    const size_t T = c.max_tokens, k = c.top_k, kk = c.top_k + c.n_shared, S = c.n_slots;
+    const size_t A = T * kk;
+    const size_t nb = (A + kAssignPerBlock - 1) / kAssignPerBlock;
+    const size_t max_tiles = (A + kMinTileRows - 1) / kMinTileRows + S;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    L.map[0] = take(4 * (c.n_experts + c.n_shared));
+    L.map[1] = take(4 * (c.n_experts + c.n_shared));
+    L.ids = take(4 * T * k);
+    L.w = take(4 * T * k);
+    L.slot_rank = take(4 * A);
+    L.blk_hist = take(4 * nb * S);
+    L.counts = take(4 * S);
+    L.offs = take(4 * (S + 1));
+    L.perm = take(4 * A);
+    L.inv = take(4 * A);
+    L.tiles = take(sizeof(MTile) * max_tiles);
+    L.n_tiles = take(4);
+    L.h = take(esize(c.act_dtype) * A * c.inter);
+    L.y = take(esize(c.act_dtype) * A * c.hidden);
+    L.total = o;
+    return L;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+}  // namespace
+
+struct moe_layer {
+    moe_config_t cfg;
+    moe_buffers_t buf;
+    Layout lay;
+    int active;      // which of the two device tables forwards read
+    bool has_map;
+    std::vector<int32_t> host_map;  // E + n_shared, copy of the active table
+};
+
+extern "C" {
+
+const char *moe_last_error(void) { return g_err; }
+
+size_t moe_workspace_bytes(const moe_config_t *cfg)
+{
+    if (check_config(cfg) != MOE_OK) return 0;
+    return make_layout(*cfg).total;
+}
+
+moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf, moe_layer_t **out)
+{
+    if (!out) return fail(MOE_ERR_ARG, "out is NULL");
+    *out = nullptr;
+    moe_status_t st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!buf) return fail(MOE_ERR_ARG, "buffers is NULL");
+    if (!buf->router_w || !buf->w13 || !buf->w2 || !buf->workspace)
+        return fail(MOE_ERR_ARG, "router_w, w13, w2 and workspace must be non-NULL");
+    if (!aligned(buf->router_w, 16) || !aligned(buf->w13, 16) || !aligned(buf->w2, 16))
+        return fail(MOE_ERR_ARG, "router_w, w13 and w2 must be 16-byte aligned");
+    if (!aligned(buf->workspace, kAlign)) return fail(MOE_ERR_ARG, "workspace must be 256-byte aligned");
+    if ((buf->logit_bias && !aligned(buf->logit_bias, 4)) || (buf->select_bias && !aligned(buf->select_bias, 4)))
+        return fail(MOE_ERR_ARG, "bias vectors must be 4-byte aligned");
+    Layout L = make_layout(*cfg);
+    if (buf->workspace_bytes < L.total)
+        return fail(MOE_ERR_CAPACITY, "workspace has %zu bytes, layer needs %zu", buf->workspace_bytes, L.total);
+    moe_layer *l = new (std::nothrow) moe_layer;
+    if (!l) return fail(MOE_ERR_ARG, "out of host memory");
+    l->cfg = *cfg;
+    l->buf = *buf;
+    l->lay = L;
+    l->active = 0;
+    l->has_map = false;
+    *out = l;
+    return MOE_OK;
+}
+
+void moe_layer_destroy(moe_layer_t *layer) { delete layer; }
+
+moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t n,
+                                const int32_t *host_shared_slots, void *hip_stream)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    if (!host_map) return fail(MOE_ERR_ARG, "host_map is NULL");
+    const moe_config_t &c = l->cfg;
+    if (n != c.n_experts) return fail(MOE_ERR_MAP, "map has %d entries, layer has %d logical experts", n, c.n_experts);
+    if ((c.n_shared > 0) != (host_shared_slots != nullptr))
+        return fail(MOE_ERR_MAP, "host_shared_slots must be given exactly when n_shared > 0");
+    std::vector<int32_t> owner(c.n_slots, -1);  // slot -> entry index that claimed it
+    std::vector<int32_t> table(c.n_experts + c.n_shared);
+    for (int e = 0; e < c.n_experts + c.n_shared; ++e) {
+        const bool shared = e >= c.n_experts;
+        const int32_t s = shared ? host_shared_slots[e - c.n_experts] : host_map[e];
+        if (s < -1 || s >= c.n_slots || (shared && s < 0))
+            return fail(MOE_ERR_MAP, "%s %d -> slot %d is outside [%s, %d)", shared ? "shared expert" : "expert",
+                        shared ? e - c.n_experts : e, s, shared ? "0" : "-1", c.n_slots);
+        if (s >= 0) {
+            if (owner[s] >= 0) return fail(MOE_ERR_MAP, "slot %d is claimed twice (entries %d and %d)", s, owner[s], e);
+            owner[s] = e;
+        }
+        table[e] = s;
+    }
+    const int target = l->has_map ? 1 - l->active : 0;
+    int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map[target]);
+    hipError_t e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
+    l->active = target;
+    l->has_map = true;
+    l->host_map.swap(table);
+    return MOE_OK;
+}
+
+moe_status_t moe_workspace_view(const moe_layer_t *l, moe_workspace_view_t *v)
+{
+    if (!l || !v) return fail(MOE_ERR_ARG, "layer or view is NULL");
+    char *ws = (char *)l->buf.workspace;
+    v->topk_ids = (const int32_t *)(ws + l->lay.ids);
+    v->topk_w = (const float *)(ws + l->lay.w);
+    v->counts = (const int32_t *)(ws + l->lay.counts);
+    v->offsets = (const int32_t *)(ws + l->lay.offs);
+    v->perm = (const int32_t *)(ws + l->lay.perm);
+    v->inv = (const int32_t *)(ws + l->lay.inv);
+    v->h = ws + l->lay.h;
+    v->y = ws + l->lay.y;
+    v->active_map = (const int32_t *)(ws + l->lay.map[l->active]);
+    return MOE_OK;
+}
+
+moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t shared_begin, int32_t shared_end,
+                         void *out, void *hip_stream, uint32_t flags)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    const moe_config_t &c = l->cfg;
+    if (T < 0) return fail(MOE_ERR_ARG, "T is negative");
+    if (T > c.max_tokens) return fail(MOE_ERR_CAPACITY, "T %d exceeds max_tokens %d", T, c.max_tokens);
+    if (shared_begin < 0 || shared_begin > shared_end || shared_end > T)
+        return fail(MOE_ERR_ARG, "shared range [%d,%d) is not inside [0,%d]", shared_begin, shared_end, T);
+    if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
+    if (!l->has_map) return fail(MOE_ERR_MAP, "no expert map installed: call moe_set_expert_map first");
+    if (T == 0) return MOE_OK;
+    if (!x || !out) return fail(MOE_ERR_ARG, "x and out must be non-NULL");
+    if (!aligned(x, 16) || !aligned(out, 16)) return fail(MOE_ERR_ARG, "x and out must be 16-byte aligned");
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = (char *)l->buf.workspace;
+    Pass p;
+    memset(&p, 0, sizeof p);
+    p.T = T; p.H = c.hidden; p.I = c.inter; p.E = c.n_experts; p.k = c.top_k; p.S = c.n_slots;
+    p.n_shared = c.n_shared; p.kk = c.top_k + c.n_shared;
+    p.act_bf16 = c.act_dtype == MOE_BF16; p.router_bf16 = c.router_dtype == MOE_BF16;
+    p.gate = c.gate; p.n_group = c.n_group; p.topk_group = c.topk_group; p.renormalize = c.renormalize;
+    p.routed_scale = c.routed_scale;
+    p.shared_begin = shared_begin; p.shared_end = shared_end;
+    p.x = x; p.out = out;
+    p.router_w = l->buf.router_w; p.logit_bias = l->buf.logit_bias; p.select_bias = l->buf.select_bias;
+    p.w13 = l->buf.w13; p.w2 = l->buf.w2;
+    p.map = (const int32_t *)(ws + l->lay.map[l->active]);
+    p.ids = (int32_t *)(ws + l->lay.ids);
+    p.w = (float *)(ws + l->lay.w);
+    p.slot_rank = (int32_t *)(ws + l->lay.slot_rank);
+    p.blk_hist = (int32_t *)(ws + l->lay.blk_hist);
+    p.counts = (int32_t *)(ws + l->lay.counts);
+    p.offs = (int32_t *)(ws + l->lay.offs);
+    p.perm = (int32_t *)(ws + l->lay.perm);
+    p.inv = (int32_t *)(ws + l->lay.inv);
+    p.tiles = (MTile *)(ws + l->lay.tiles);
+    p.n_tiles = (int32_t *)(ws + l->lay.n_tiles);
+    p.h = ws + l->lay.h;
+    p.y = ws + l->lay.y;
+
+    const bool identity = flags & MOE_FLAG_IDENTITY_EXPERTS;
+    const int tile_rows = kGenericTileRows;
+    p.max_tiles = (int)(((long long)T * p.kk + tile_rows - 1) / tile_rows) + p.S;
+
+    hipError_t e;
+    if ((e = launch_gate(p, st)) != hipSuccess) return fail(MOE_ERR_HIP, "gate launch: %s", hipGetErrorString(e));
+    if ((e = launch_permute(p, tile_rows, st)) != hipSuccess) return fail(MOE_ERR_HIP, "permute launch: %s", hipGetErrorString(e));
+    if (identity) e = launch_identity_experts(p, st);
+    else          e = launch_experts_generic(p, st);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert launch: %s", hipGetErrorString(e));
+    if ((e = launch_combine(p, st)) != hipSuccess) return fail(MOE_ERR_HIP, "combine launch: %s", hipGetErrorString(e));
+    return MOE_OK;
+}
+
+}  // extern "C"

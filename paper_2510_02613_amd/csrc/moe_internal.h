@@ -1,0 +1,83 @@
+// Internal declarations shared by the translation units of libelasticmoe.so.
+// Host-side launch wrappers only; every kernel lives in its own .hip file.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "elasticmoe.h"
+
+namespace emoe {
+
+// One M-tile of the grouped GEMMs: `rows` consecutive grouped rows starting at
+// `row_begin`, all belonging to weight slot `slot`.
+struct MTile {
+    int32_t slot;
+    int32_t row_begin;
+    int32_t rows;
+    int32_t pad;
+};
+
+// Everything the kernels need to know about one forward pass.  Plain device
+// pointers into caller-owned memory (x/out/weights) and the caller's workspace.
+struct Pass {
+    // layer
+    int32_t T, H, I, E, k, S, kk;  // kk = k + n_shared : assignment columns per token
+    int32_t n_shared;
+    int32_t act_bf16, router_bf16;
+    int32_t gate, n_group, topk_group, renormalize;
+    float routed_scale;
+    int32_t shared_begin, shared_end;
+    // caller buffers
+    const void *x;
+    void *out;
+    const void *router_w;
+    const float *logit_bias, *select_bias;
+    const void *w13, *w2;
+    // workspace
+    const int32_t *map;  // [E + n_shared] active table, shared slots last
+    int32_t *ids;        // [T,k]
+    float *w;            // [T,k]
+    int32_t *slot_rank;  // [T*kk] (slot << 12 | rank-in-block) or -1
+    int32_t *blk_hist;   // [NB,S] per-block histogram, then per-block exclusive base
+    int32_t *counts;     // [S]
+    int32_t *offs;       // [S+1]
+    int32_t *perm;       // [A]
+    int32_t *inv;        // [T,kk]
+    MTile *tiles;        // [max_tiles]
+    int32_t *n_tiles;    // [1]
+    void *h;             // [A,I]
+    void *y;             // [A,H]
+    int32_t max_tiles;
+};
+
+constexpr int kAssignPerBlock = 256;  // assignments ranked by one block of the permute kernels
+
+hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st);
+hipError_t launch_gate(const Pass &p, hipStream_t st);
+hipError_t launch_permute(const Pass &p, int tile_rows, hipStream_t st);
+hipError_t launch_experts_generic(const Pass &p, hipStream_t st);
+hipError_t launch_identity_experts(const Pass &p, hipStream_t st);
+hipError_t launch_combine(const Pass &p, hipStream_t st);
+
+constexpr int kGenericTileRows = 32;  // M-tile of the plain expert kernels
+
+// ---- small device helpers ---------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest, ties to even
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T *p, size_t i);
+template <> __device__ __forceinline__ float load_f32<float>(const float *p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float load_f32<uint16_t>(const uint16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+
+template <typename T> __device__ __forceinline__ void store_f32(T *p, size_t i, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float *p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void store_f32<uint16_t>(uint16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+}  // namespace emoe

@@ -1,0 +1,171 @@
+"""Shared helpers of the GPU parity tests: build a layer from a seeded workload,
+run it through the C ABI, and grade it against the CPU oracle."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from oracle import LayerSpec
+from workloads import (MoEWorkload, make_inputs, build_slot_pool, bf16_bits_to_f32,
+                       block_expert_map, shared_slots_of)
+
+TOL = {"bf16": 1e-2, "f32": 1e-4}   # max-relative-error bar on the layer output
+W_ATOL = 1e-5                        # combine weights, times routed_scale
+TIE = 1e-5                           # fp32 score gap under which a routing flip is legal
+
+
+def to_f64(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.uint16:
+        return bf16_bits_to_f32(a).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def tensor_to_host(t):
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
+class Case:
+    """A workload instantiated on the GPU plus everything the oracle needs."""
+
+    def __init__(self, wl: MoEWorkload, expert_map=None, shared_slots=None, inputs=None,
+                 select_bias=None, max_tokens=None):
+        from paper_2510_02613_amd.layer import MoELayer
+        self.wl = wl
+        self.inp = make_inputs(wl) if inputs is None else inputs
+        self.spec = LayerSpec.from_workload(wl)
+        self.expert_map = (block_expert_map(wl.n_experts, 0, min(wl.n_local, wl.n_slots - wl.n_shared))
+                           if expert_map is None else np.asarray(expert_map, np.int32))
+        self.shared_slots = shared_slots_of(wl) if shared_slots is None else np.asarray(shared_slots, np.int32)
+        self.select_bias = select_bias
+        self.layer = MoELayer(hidden=wl.hidden, inter=wl.inter, n_experts=wl.n_experts, top_k=wl.top_k,
+                              n_slots=wl.n_slots, max_tokens=max_tokens or max(wl.tokens, 1),
+                              act_dtype=wl.act_dtype, router_dtype=wl.router_dtype, gate=wl.gate,
+                              n_group=wl.n_group, topk_group=wl.topk_group, renormalize=wl.renormalize,
+                              routed_scale=wl.routed_scale, n_shared=wl.n_shared,
+                              router_w=self.inp["router_w"], logit_bias=self.inp["logit_bias"],
+                              select_bias=select_bias)
+        self.place(self.expert_map, self.shared_slots)
+        self.x_dev = self.layer.upload(self.inp["x"])
+
+    def place(self, expert_map, shared_slots=None, upload=True):
+        """(Re)build the slot pools for a placement and install the map."""
+        wl = self.wl
+        self.expert_map = np.asarray(expert_map, np.int32)
+        if shared_slots is not None:
+            self.shared_slots = np.asarray(shared_slots, np.int32)
+        self.w13_pool = build_slot_pool(self.inp["w13_experts"], self.expert_map, wl.n_slots, wl.n_local, self.shared_slots)
+        self.w2_pool = build_slot_pool(self.inp["w2_experts"], self.expert_map, wl.n_slots, wl.n_local, self.shared_slots)
+        if upload:
+            self.layer.load_pool(self.w13_pool, self.w2_pool)
+        self.layer.set_expert_map(self.expert_map, self.shared_slots if wl.n_shared else None)
+
+    def run(self, flags=0, T=None, shared_range=None):
+        import torch
+        T = self.wl.tokens if T is None else T
+        sr = self.wl.shared_range if shared_range is None else shared_range
+        out = self.layer.forward(self.x_dev[:T], shared_range=sr, flags=flags)
+        torch.cuda.synchronize()
+        return tensor_to_host(out)
+
+    # ---- oracle side ---------------------------------------------------------
+    def oracle_route(self):
+        return oracle.route(self.spec, self.inp["x"], self.inp["router_w"], self.inp["logit_bias"],
+                            self.select_bias, want_scores=True)
+
+    def oracle_forward(self, tokens=None, forced_ids=None, identity=False, shared_range=None):
+        sr = self.wl.shared_range if shared_range is None else shared_range
+        return oracle.forward(self.spec, self.inp["x"], self.inp["router_w"], self.w13_pool, self.w2_pool,
+                              self.expert_map, logit_bias=self.inp["logit_bias"], select_bias=self.select_bias,
+                              shared_slots=self.shared_slots, shared_range=sr, tokens=tokens,
+                              forced_ids=forced_ids, identity_experts=identity)
+
+
+def check_routing(case: Case, gpu_ids: np.ndarray, gpu_w: np.ndarray):
+    """Routing parity: identical expert sets on every unflagged token; on flagged tokens a
+    difference must be a swap of candidates whose fp32 scores lie within TIE of the k-th
+    score.  Weights agree to W_ATOL * scale per expert.  Returns (ids to grade the output
+    with, number of flagged tokens, number of legal flips)."""
+    o_ids, o_w, flags, c = case.oracle_route()
+    T, k = o_ids.shape
+    assert gpu_ids.shape == (T, k)
+    assert (gpu_ids >= 0).all() and (gpu_ids < case.wl.n_experts).all()
+    srt_g, srt_o = np.sort(gpu_ids, 1), np.sort(o_ids, 1)
+    assert (np.diff(srt_g, axis=1) > 0).all(), "a token selected the same expert twice"
+    differ = (srt_g != srt_o).any(1)
+    bad = differ & (flags == 0)
+    assert not bad.any(), f"routing differs on unflagged tokens {np.nonzero(bad)[0][:8]}"
+    flips = 0
+    for t in np.nonzero(differ)[0]:
+        only_g = set(gpu_ids[t]) - set(o_ids[t])
+        only_o = set(o_ids[t]) - set(gpu_ids[t])
+        kth = c[t, o_ids[t, -1]]
+        if flags[t] & 2:
+            continue  # group near-tie: whole groups may swap; output graded with the GPU's ids
+        for e in only_g | only_o:
+            assert abs(float(c[t, e]) - float(kth)) < TIE, (t, e, c[t, e], kth)
+        flips += 1
+    # weights, matched per expert id (positions may differ among near-equal scores)
+    scale = abs(case.wl.routed_scale)
+    same = ~differ
+    og = np.argsort(gpu_ids, 1)
+    oo = np.argsort(o_ids, 1)
+    wg = np.take_along_axis(gpu_w.astype(np.float64), og, 1)
+    wo = np.take_along_axis(o_w, oo, 1)
+    err = np.abs(wg - wo)[same]
+    assert err.max(initial=0.0) <= W_ATOL * scale, f"weight error {err.max()}"
+    return gpu_ids, int((flags != 0).sum()), flips
+
+
+def check_bookkeeping(case: Case, v: dict, T: int, shared_range):
+    """counts / offsets / perm / inv against their definitions, from the GPU's own ids."""
+    wl = case.wl
+    k, kk, S = wl.top_k, wl.top_k + wl.n_shared, wl.n_slots
+    ids = v["topk_ids"]
+    slot = np.full((T, kk), -1, np.int64)
+    slot[:, :k] = case.expert_map[ids]
+    for i in range(wl.n_shared):
+        slot[shared_range[0]:shared_range[1], k + i] = case.shared_slots[i]
+    np.testing.assert_array_equal(v["active_map"], np.concatenate([case.expert_map, case.shared_slots[:wl.n_shared]]))
+    counts = np.bincount(slot[slot >= 0], minlength=S)
+    np.testing.assert_array_equal(v["counts"], counts)
+    np.testing.assert_array_equal(v["offsets"], np.concatenate([[0], np.cumsum(counts)]))
+    A = int(counts.sum())
+    inv = v["inv"]
+    np.testing.assert_array_equal(inv >= 0, slot >= 0)
+    rows = inv[inv >= 0]
+    assert rows.size == A and np.array_equal(np.sort(rows), np.arange(A)), "inv is not a bijection onto [0,A)"
+    tok = np.repeat(np.arange(T)[:, None], kk, 1)
+    np.testing.assert_array_equal(v["perm"][rows], tok[inv >= 0])
+    offs = v["offsets"]
+    s_of_row = np.searchsorted(offs, rows, side="right") - 1
+    np.testing.assert_array_equal(s_of_row, slot[inv >= 0])
+    # rows of one slot are ordered by (token, position): deterministic layout
+    for s in range(S):
+        r = inv[slot == s]
+        assert (np.diff(r) > 0).all()
+
+
+def rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """max |got - want| / max |want| over the whole array."""
+    den = np.abs(want).max()
+    if den == 0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - want).max() / den)
+
+
+def check_output(case: Case, out_bits: np.ndarray, grade_ids: np.ndarray, tokens=None, identity=False,
+                 shared_range=None):
+    want = case.oracle_forward(tokens=tokens, forced_ids=grade_ids, identity=identity, shared_range=shared_range)
+    got = to_f64(out_bits if tokens is None else out_bits[np.asarray(tokens)])
+    assert np.isfinite(got).all()
+    err = rel_err(got, want)
+    tol = TOL[case.wl.act_dtype]
+    assert err <= tol, f"max relative error {err:.3e} > {tol}"
+    # per-row view of the same bar (rows whose reference is all zero must be exactly zero)
+    ref_max = np.abs(want).max(1)
+    zero = ref_max == 0
+    assert (got[zero] == 0).all()
+    row_err = np.abs(got - want).max(1)[~zero] / np.abs(want).max()
+    assert row_err.max(initial=0.0) <= tol
+    return err

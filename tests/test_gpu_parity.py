@@ -1,0 +1,176 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same
+seeded inputs.  Integer results (routing, bookkeeping) are bit exact up to flagged score
+near-ties; outputs meet max-relative-error 1e-2 (bf16) / 1e-4 (fp32)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from workloads import MoEWorkload, get_workload, block_expert_map, relayout_maps
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(wl, **kw):
+    from gpu_util import Case
+    return Case(wl, **kw)
+
+
+def _full_check(case, flags=0, sample=None, T=None, shared_range=None):
+    from gpu_util import check_routing, check_bookkeeping, check_output
+    wl = case.wl
+    T = wl.tokens if T is None else T
+    sr = wl.shared_range if shared_range is None else shared_range
+    out = case.run(flags=flags, T=T, shared_range=sr)
+    v = case.layer.view(T)
+    if T == wl.tokens:
+        grade_ids, n_flag, flips = check_routing(case, v["topk_ids"], v["topk_w"])
+    else:
+        grade_ids, n_flag, flips = None, 0, 0
+    check_bookkeeping(case, v, T, sr)
+    tokens = None if T == wl.tokens else np.arange(T, dtype=np.int32)
+    if sample is not None and sample < T:
+        g = np.random.Generator(np.random.PCG64(1234 + wl.seed))
+        tokens = np.sort(g.choice(T, size=sample, replace=False)).astype(np.int32)
+    err = check_output(case, out, grade_ids, tokens=tokens, shared_range=sr)
+    return out, v, err
+
+
+SMALL = dict(hidden=256, inter=136, n_experts=16, top_k=4, n_slots=16, n_local=16,
+             act_dtype="bf16", router_dtype="f32", gate="softmax", seed=11)
+
+
+def test_tiny_f32_workload_all_tokens():
+    case = _case(get_workload("tiny_f32"))
+    _full_check(case)
+
+
+@pytest.mark.parametrize("tokens", [1, 7, 300, 1000])
+def test_small_bf16_softmax_ragged(tokens):
+    wl = MoEWorkload(name="small", tokens=tokens, **SMALL)
+    _full_check(_case(wl))
+
+
+def test_small_f32_ragged_tiles():
+    wl = MoEWorkload(name="small32", tokens=333, **{**SMALL, "act_dtype": "f32", "hidden": 136, "inter": 72})
+    _full_check(_case(wl))
+
+
+def test_small_grouped_sigmoid_with_shared_expert_and_partial_locality():
+    wl = MoEWorkload(name="smallg", tokens=515, hidden=256, inter=136, n_experts=32, top_k=4,
+                     n_slots=9, n_local=8, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=4, topk_group=2, routed_scale=2.5, n_shared=1,
+                     shared_range=(100, 317), seed=12)
+    case = _case(wl)
+    out, v, _ = _full_check(case)
+    # tokens with no local expert and outside the shared range are exact zero rows
+    local = (case.expert_map[v["topk_ids"]] >= 0).any(1)
+    outside = np.ones(wl.tokens, bool)
+    outside[100:317] = False
+    assert (outside & ~local).any()
+    assert (out[outside & ~local] == 0).all()
+
+
+def test_no_renormalise_scale_and_select_bias():
+    wl = MoEWorkload(name="smallb", tokens=200, **{**SMALL, "renormalize": False, "routed_scale": 1.5})
+    sb = np.zeros(16, np.float32)
+    sb[3] = 0.5
+    case = _case(wl, select_bias=sb)
+    out, v, _ = _full_check(case)
+    assert (v["topk_ids"] == 3).any(1).all()
+
+
+def test_identity_experts_return_weighted_input():
+    from gpu_util import check_output, check_routing, to_f64
+    from paper_2510_02613_amd import MOE_FLAG_IDENTITY_EXPERTS
+    wl = MoEWorkload(name="ident", tokens=300, **{**SMALL, "act_dtype": "f32"})
+    case = _case(wl)
+    out = case.run(flags=MOE_FLAG_IDENTITY_EXPERTS)
+    v = case.layer.view(wl.tokens)
+    ids, _, _ = check_routing(case, v["topk_ids"], v["topk_w"])
+    check_output(case, out, ids, identity=True)
+    # all experts local, weights renormalised: the layer returns its input
+    np.testing.assert_allclose(out, case.inp["x"], rtol=0, atol=2e-6 * np.abs(case.inp["x"]).max())
+
+
+def test_slot_permutation_is_bit_identical():
+    wl = MoEWorkload(name="perm", tokens=400, **{**SMALL, "n_slots": 24})
+    case = _case(wl)
+    a = case.run()
+    g = np.random.Generator(np.random.PCG64(5))
+    case.place(g.permutation(24)[:16].astype(np.int32))
+    b = case.run()
+    np.testing.assert_array_equal(a, b)
+
+
+def test_empty_token_batch_and_capacity_errors():
+    from paper_2510_02613_amd import MoEError, MOE_ERR_CAPACITY, MOE_ERR_ARG
+    wl = MoEWorkload(name="edge", tokens=64, **SMALL)
+    case = _case(wl)
+    out = case.layer.forward(case.x_dev[:0])
+    assert out.shape[0] == 0
+    with pytest.raises(MoEError) as ei:
+        case.layer.forward(case.x_dev.repeat(2, 1))
+    assert ei.value.status == MOE_ERR_CAPACITY
+    with pytest.raises(MoEError) as ei:
+        case.layer.forward(case.x_dev, shared_range=(0, 65))
+    assert ei.value.status == MOE_ERR_ARG
+    _full_check(case)  # the layer still works after rejected calls
+
+
+def test_all_experts_remote_gives_zero_output():
+    wl = MoEWorkload(name="remote", tokens=50, **SMALL)
+    case = _case(wl, expert_map=np.full(16, -1, np.int32))
+    out = case.run()
+    assert (out == 0).all()
+    v = case.layer.view(50)
+    assert v["counts"].sum() == 0 and (v["inv"] == -1).all()
+
+
+def test_shorter_batch_than_capacity_after_longer_one():
+    wl = MoEWorkload(name="reuse", tokens=300, **SMALL)
+    case = _case(wl)
+    _full_check(case)
+    _full_check(case, T=77)
+
+
+# ---- the five benchmark configurations at full size ---------------------------
+
+def test_qwen3_shape_full_size_sampled():
+    case = _case(get_workload("qwen3_30b_a3b"))
+    _, v, err = _full_check(case, sample=48)
+    assert v["offsets"][-1] == 4096 * 8
+
+
+def test_dsv3_rank_full_size_sampled():
+    case = _case(get_workload("dsv3_ep8_rank"))
+    _full_check(case, sample=64)
+
+
+def test_dsv3_decode_all_tokens():
+    case = _case(get_workload("dsv3_ep8_decode"))
+    _, v, _ = _full_check(case)
+    assert v["counts"][:32].max() <= 16
+
+
+def test_relayout_switch_keeps_buffers_and_matches_oracle():
+    import torch
+    wl = get_workload("qwen3_relayout")
+    map_a, map_b = relayout_maps(wl)
+    case = _case(wl, expert_map=map_a)
+    _full_check(case, sample=48)
+    ptrs = (case.layer.w13.data_ptr(), case.layer.w2.data_ptr(), case.layer.workspace.data_ptr())
+    free0, _ = torch.cuda.mem_get_info()
+    alloc0 = torch.cuda.memory_stats()["allocation.all.allocated"]
+    # copy experts 32..63 into their (shuffled) free slots, then flip the table
+    for e in range(32, 64):
+        case.layer.load_slot(int(map_b[e]), case.inp["w13_experts"][e], case.inp["w2_experts"][e])
+    base_alloc = torch.cuda.memory_stats()["allocation.all.allocated"]
+    case.place(map_b, upload=False)
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == base_alloc  # the switch allocates nothing
+    assert ptrs == (case.layer.w13.data_ptr(), case.layer.w2.data_ptr(), case.layer.workspace.data_ptr())
+    # the pool on the device now equals the pool the oracle was given
+    from gpu_util import tensor_to_host
+    np.testing.assert_array_equal(tensor_to_host(case.layer.w13[40:42]), case.w13_pool[40:42])
+    _full_check(case, sample=48)
+    assert alloc0 <= base_alloc
