@@ -171,6 +171,20 @@ moe_status_t moe_forward(moe_layer_t *layer, const void *x, int32_t T,
 /* Addresses of the intermediates (valid for the layer's lifetime). */
 moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *view);
 
+/*
+ * Phase timing for benchmarks (not part of the method; it exists so that a
+ * benchmark can time each kernel of a pass on the very stream the pass runs on).
+ * While enabled, every moe_forward records HIP events around its phases; the last
+ * 64 forwards are kept.  moe_profile_read waits for the forward `back` passes ago
+ * (0 = most recent) and writes the milliseconds of each phase to ms[MOE_N_PHASES].
+ * Enabling creates the events (host objects), disabling or destroying the layer
+ * destroys them.
+ */
+enum { MOE_PHASE_GATE = 0, MOE_PHASE_PERMUTE = 1, MOE_PHASE_GEMM1 = 2, MOE_PHASE_GEMM2 = 3,
+       MOE_PHASE_COMBINE = 4, MOE_N_PHASES = 5 };
+moe_status_t moe_profile_enable(moe_layer_t *layer, int32_t enable);
+moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
+
 /* Frees the host object only (the library owns no device memory). NULL is allowed. */
 void moe_layer_destroy(moe_layer_t *layer);
 

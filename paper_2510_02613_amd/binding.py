@@ -22,7 +22,10 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_M
 
 # every symbol include/elasticmoe.h declares
 EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
-           "moe_workspace_view", "moe_layer_destroy", "moe_last_error")
+           "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
+           "moe_profile_read")
+MOE_N_PHASES = 5
+PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
 
 
 class MoEConfig(ctypes.Structure):
@@ -77,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.moe_workspace_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(MoEWorkspaceView)]
         L.moe_layer_destroy.restype = None
         L.moe_layer_destroy.argtypes = [ctypes.c_void_p]
+        L.moe_profile_enable.restype = ctypes.c_int
+        L.moe_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        L.moe_profile_read.restype = ctypes.c_int
+        L.moe_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_last_error.argtypes = []
         _lib = L
@@ -131,6 +138,16 @@ def moe_workspace_view(layer) -> MoEWorkspaceView:
     v = MoEWorkspaceView()
     _check(lib().moe_workspace_view(layer, ctypes.byref(v)))
     return v
+
+
+def moe_profile_enable(layer, enable: bool) -> None:
+    _check(lib().moe_profile_enable(layer, int(bool(enable))))
+
+
+def moe_profile_read(layer, back: int = 0):
+    ms = (ctypes.c_float * MOE_N_PHASES)()
+    _check(lib().moe_profile_read(layer, back, ms))
+    return [float(v) for v in ms]
 
 
 def moe_layer_destroy(layer) -> None:

@@ -104,16 +104,16 @@ __global__ __launch_bounds__(256) void k_identity_experts(Pass p)
 
 }  // namespace
 
-hipError_t launch_experts_generic(const Pass &p, hipStream_t st)
+hipError_t launch_experts_generic(const Pass &p, int which, hipStream_t st)
 {
     dim3 block(kThreads);
     dim3 g1((p.I + kBN - 1) / kBN, p.max_tiles), g2((p.H + kBN - 1) / kBN, p.max_tiles);
     if (p.act_bf16) {
-        hipLaunchKernelGGL((k_expert_gemm_generic<uint16_t, true>), g1, block, 0, st, p);
-        hipLaunchKernelGGL((k_expert_gemm_generic<uint16_t, false>), g2, block, 0, st, p);
+        if (which == 0) hipLaunchKernelGGL((k_expert_gemm_generic<uint16_t, true>), g1, block, 0, st, p);
+        else            hipLaunchKernelGGL((k_expert_gemm_generic<uint16_t, false>), g2, block, 0, st, p);
     } else {
-        hipLaunchKernelGGL((k_expert_gemm_generic<float, true>), g1, block, 0, st, p);
-        hipLaunchKernelGGL((k_expert_gemm_generic<float, false>), g2, block, 0, st, p);
+        if (which == 0) hipLaunchKernelGGL((k_expert_gemm_generic<float, true>), g1, block, 0, st, p);
+        else            hipLaunchKernelGGL((k_expert_gemm_generic<float, false>), g2, block, 0, st, p);
     }
     return hipGetLastError();
 }

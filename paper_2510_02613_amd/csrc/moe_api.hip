@@ -99,7 +99,12 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 }  // namespace
 
+constexpr int kProfRing = 64;  // forwards whose phase events are kept
+
 struct moe_layer {
+    bool prof_on = false;
+    long long prof_count = 0;  // forwards recorded since profiling was enabled
+    hipEvent_t ev[kProfRing][MOE_N_PHASES + 1] = {};
     moe_config_t cfg;
     moe_buffers_t buf;
     Layout lay;
@@ -146,7 +151,54 @@ moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf,
     return MOE_OK;
 }
 
-void moe_layer_destroy(moe_layer_t *layer) { delete layer; }
+void moe_layer_destroy(moe_layer_t *layer)
+{
+    if (!layer) return;
+    if (layer->prof_on) moe_profile_enable(layer, 0);
+    delete layer;
+}
+
+moe_status_t moe_profile_enable(moe_layer_t *l, int32_t enable)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    if ((enable != 0) == l->prof_on) return MOE_OK;
+    if (enable) {
+        for (int i = 0; i < kProfRing; ++i)
+            for (int j = 0; j <= MOE_N_PHASES; ++j) {
+                hipError_t e = hipEventCreate(&l->ev[i][j]);
+                if (e != hipSuccess) {
+                    for (int a = 0; a <= i; ++a)
+                        for (int b = 0; b <= MOE_N_PHASES; ++b)
+                            if (l->ev[a][b]) { (void)hipEventDestroy(l->ev[a][b]); l->ev[a][b] = nullptr; }
+                    return fail(MOE_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+                }
+            }
+        l->prof_count = 0;
+        l->prof_on = true;
+    } else {
+        for (int i = 0; i < kProfRing; ++i)
+            for (int j = 0; j <= MOE_N_PHASES; ++j)
+                if (l->ev[i][j]) { (void)hipEventDestroy(l->ev[i][j]); l->ev[i][j] = nullptr; }
+        l->prof_on = false;
+    }
+    return MOE_OK;
+}
+
+moe_status_t moe_profile_read(moe_layer_t *l, int32_t back, float *ms)
+{
+    if (!l || !ms) return fail(MOE_ERR_ARG, "layer or ms is NULL");
+    if (!l->prof_on) return fail(MOE_ERR_ARG, "profiling is not enabled on this layer");
+    if (back < 0 || back >= kProfRing || back >= l->prof_count)
+        return fail(MOE_ERR_ARG, "no recorded forward %d steps back (recorded %lld, kept %d)", back, l->prof_count, kProfRing);
+    hipEvent_t *ev = l->ev[(l->prof_count - 1 - back) % kProfRing];
+    hipError_t e = hipEventSynchronize(ev[MOE_N_PHASES]);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
+    for (int j = 0; j < MOE_N_PHASES; ++j) {
+        e = hipEventElapsedTime(&ms[j], ev[j], ev[j + 1]);
+        if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
+    }
+    return MOE_OK;
+}
 
 moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t n,
                                 const int32_t *host_shared_slots, void *hip_stream)
@@ -240,16 +292,31 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     p.y = ws + l->lay.y;
 
     const bool identity = flags & MOE_FLAG_IDENTITY_EXPERTS;
-    const int tile_rows = kGenericTileRows;
+    const bool mfma = p.act_bf16 && !(flags & MOE_FLAG_FORCE_GENERIC);
+    const int tile_rows = mfma ? mfma_tile_rows() : kGenericTileRows;
     p.max_tiles = (int)(((long long)T * p.kk + tile_rows - 1) / tile_rows) + p.S;
 
-    hipError_t e;
-    if ((e = launch_gate(p, st)) != hipSuccess) return fail(MOE_ERR_HIP, "gate launch: %s", hipGetErrorString(e));
-    if ((e = launch_permute(p, tile_rows, st)) != hipSuccess) return fail(MOE_ERR_HIP, "permute launch: %s", hipGetErrorString(e));
-    if (identity) e = launch_identity_experts(p, st);
-    else          e = launch_experts_generic(p, st);
-    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert launch: %s", hipGetErrorString(e));
-    if ((e = launch_combine(p, st)) != hipSuccess) return fail(MOE_ERR_HIP, "combine launch: %s", hipGetErrorString(e));
+    // optional phase events (benchmarks): event j is recorded before phase j, the last one after the pass
+    hipEvent_t *ev = l->prof_on ? l->ev[l->prof_count % kProfRing] : nullptr;
+    hipError_t e = hipSuccess;
+    auto mark = [&](int j) { if (ev && e == hipSuccess) e = hipEventRecord(ev[j], st); };
+    mark(MOE_PHASE_GATE);
+    if (e == hipSuccess) e = launch_gate(p, st);
+    mark(MOE_PHASE_PERMUTE);
+    if (e == hipSuccess) e = launch_permute(p, tile_rows, st);
+    mark(MOE_PHASE_GEMM1);
+    if (e == hipSuccess) {
+        if (identity)  e = launch_identity_experts(p, st);
+        else if (mfma) e = launch_experts_mfma(p, 0, st);
+        else           e = launch_experts_generic(p, 0, st);
+    }
+    mark(MOE_PHASE_GEMM2);
+    if (e == hipSuccess && !identity) e = mfma ? launch_experts_mfma(p, 1, st) : launch_experts_generic(p, 1, st);
+    mark(MOE_PHASE_COMBINE);
+    if (e == hipSuccess) e = launch_combine(p, st);
+    mark(MOE_N_PHASES);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
+    if (ev) l->prof_count++;
     return MOE_OK;
 }
 

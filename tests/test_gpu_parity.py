@@ -174,3 +174,26 @@ def test_relayout_switch_keeps_buffers_and_matches_oracle():
     np.testing.assert_array_equal(tensor_to_host(case.layer.w13[40:42]), case.w13_pool[40:42])
     _full_check(case, sample=48)
     assert alloc0 <= base_alloc
+
+
+def test_plain_expert_kernels_on_bf16_layer():
+    """The non-MFMA expert kernels stay correct for bf16 layers (debugging path)."""
+    from paper_2510_02613_amd import MOE_FLAG_FORCE_GENERIC
+    wl = MoEWorkload(name="generic", tokens=300, **SMALL)
+    _full_check(_case(wl), flags=MOE_FLAG_FORCE_GENERIC)
+
+
+def test_phase_timing_reports_every_phase():
+    from paper_2510_02613_amd import binding as B
+    wl = MoEWorkload(name="prof", tokens=300, **SMALL)
+    case = _case(wl)
+    B.moe_profile_enable(case.layer.handle, True)
+    for _ in range(3):
+        case.run()
+    for back in range(3):
+        ms = B.moe_profile_read(case.layer.handle, back)
+        assert len(ms) == 5 and all(0 <= v < 1000 for v in ms) and sum(ms) > 0
+    with pytest.raises(B.MoEError):
+        B.moe_profile_read(case.layer.handle, 3)
+    B.moe_profile_enable(case.layer.handle, False)
+    _full_check(case)
