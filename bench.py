@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE rank layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one whole forward pass of the layer (gate, permute, both grouped expert
+GEMMs, combine) over one batch of synthetic tokens that is already resident in
+HBM.  Prints ONE JSON line: whole-layer tokens/s, the roofline position of the
+dominant kernel (timed with HIP events on the pass's own stream, inside the timed
+region) and the fp64 CPU oracle timed on a bounded token sample of the same
+workload on this machine's host cores.
+
+Only one GPU is used: the layer is one expert-parallel rank's share of the work.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# published MI355X peaks
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc runs (FETCH_SIZE and
+# WRITE_SIZE, scaled by the factor a plain copy of known size gives): bytes, or None when no
+# counter run has been recorded for that workload.  The summaries sit under profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="qwen3_30b_a3b",
+                    help="qwen3_30b_a3b (headline) | dsv3_ep8_rank | dsv3_ep8_decode | qwen3_relayout | tiny_f32")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-phase-events", action="store_true",
+                    help="do not record per-kernel events inside the timed region (roofline then is null)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 1 GiB device copy (counter calibration for rocprofv3 --pmc) and exit")
+    return ap.parse_args()
+
+
+def algorithmic_work(wl, counts, shared_rows):
+    """Useful flops and minimum HBM bytes of one pass (no padding rows, every needed byte once)."""
+    H, I, E, T = wl.hidden, wl.inter, wl.n_experts, wl.tokens
+    es = 2 if wl.act_dtype == "bf16" else 4
+    rs = 2 if wl.router_dtype == "bf16" else 4
+    A = int(counts.sum())
+    active = int((counts > 0).sum())
+    flops_gemm1 = 4.0 * H * I * A
+    flops_gemm2 = 2.0 * H * I * A
+    flops_gate = 2.0 * T * H * E
+    bytes_w13 = active * 2 * I * H * es
+    bytes_w2 = active * H * I * es
+    return {
+        "assignments": A, "active_slots": active,
+        "flops_gemm1": flops_gemm1, "flops_gemm2": flops_gemm2, "flops_gate": flops_gate,
+        "flops_total": flops_gemm1 + flops_gemm2 + flops_gate,
+        # GEMM-1 reads its weights once, gathers each token row once per assignment, writes h
+        "bytes_gemm1": bytes_w13 + A * H * es + A * I * es,
+        "bytes_gemm2": bytes_w2 + A * I * es + A * H * es,
+        # whole layer minimum: weights + router + x in + out
+        "bytes_layer_min": bytes_w13 + bytes_w2 + E * H * rs + 2 * T * H * es,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one expert-parallel rank on ONE GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_each_way": n, "launches": 5}))
+        return
+
+    from workloads import get_workload, make_inputs, relayout_maps, block_expert_map, shared_slots_of, build_slot_pool
+    from paper_2510_02613_amd import binding as B
+    from paper_2510_02613_amd.layer import MoELayer
+
+    wl = get_workload(args.workload)
+    inp = make_inputs(wl, threads=16)
+    if wl.name == "qwen3_relayout":
+        expert_map = relayout_maps(wl)[1]
+    else:
+        expert_map = block_expert_map(wl.n_experts, 0, wl.n_local)
+    shared = shared_slots_of(wl)
+    layer = MoELayer(hidden=wl.hidden, inter=wl.inter, n_experts=wl.n_experts, top_k=wl.top_k,
+                     n_slots=wl.n_slots, max_tokens=wl.tokens, act_dtype=wl.act_dtype,
+                     router_dtype=wl.router_dtype, gate=wl.gate, n_group=wl.n_group,
+                     topk_group=wl.topk_group, renormalize=wl.renormalize, routed_scale=wl.routed_scale,
+                     n_shared=wl.n_shared, router_w=inp["router_w"], logit_bias=inp["logit_bias"], device=dev)
+    w13_pool = build_slot_pool(inp["w13_experts"], expert_map, wl.n_slots, wl.n_local, shared)
+    w2_pool = build_slot_pool(inp["w2_experts"], expert_map, wl.n_slots, wl.n_local, shared)
+    layer.load_pool(w13_pool, w2_pool)
+    layer.set_expert_map(expert_map, shared if wl.n_shared else None)
+    x = layer.upload(inp["x"])
+    out = torch.empty_like(x)
+    stream = torch.cuda.current_stream(dev)
+
+    def step():
+        layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    use_events = not args.no_phase_events
+    if use_events:
+        B.moe_profile_enable(layer.handle, True)
+        step()  # events exist now; keep their first use out of the timed region
+        torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    phases = None
+    if use_events:
+        n = min(args.steps, 64)
+        acc = np.zeros(B.MOE_N_PHASES)
+        for back in range(n):
+            acc += np.array(B.moe_profile_read(layer.handle, back))
+        phases = dict(zip(B.PHASE_NAMES, (acc / n).tolist()))
+        B.moe_profile_enable(layer.handle, False)
+
+    view = layer.view(wl.tokens)
+    counts = view["counts"]
+    work = algorithmic_work(wl, counts, wl.shared_range[1] - wl.shared_range[0])
+    decode = wl.name == "dsv3_ep8_decode"
+
+    roofline = None
+    if phases:
+        dom = "gemm1"
+        t_dom = phases[dom] * 1e-3
+        if decode:
+            ach = work["bytes_gemm1"] / t_dom / 1e9
+            roofline = {"bound": "hbm", "kernel": "grouped GEMM-1 + SwiGLU", "achieved": ach, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+        else:
+            ach = work["flops_gemm1"] / t_dom / 1e12
+            roofline = {"bound": "mfma", "kernel": "grouped GEMM-1 + SwiGLU", "achieved": ach,
+                        "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_MFMA_TFLOPS}
+        roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(wl.name)
+        roofline["avg_launch_us"] = phases[dom] * 1e3
+        roofline["algorithmic_per_launch"] = work["bytes_gemm1"] if decode else work["flops_gemm1"]
+
+    result = {
+        "metric": "MoE layer tokens/s at 1 MI355X; % bf16 MFMA peak (prefill), % HBM BW (decode)",
+        "value": wl.tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.act_dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
+                   "n_experts": wl.n_experts, "top_k": wl.top_k, "local_slots": int((expert_map >= 0).sum()) + wl.n_shared,
+                   "gate": wl.gate, "assignments": work["assignments"], "active_slots": work["active_slots"],
+                   "rows_per_slot_max": int(counts.max()), "rows_per_slot_mean": float(counts[counts > 0].mean()) if (counts > 0).any() else 0.0},
+        "layer": {"tflops": work["flops_total"] / (ms_per_step * 1e-3) / 1e12,
+                  "frac_bf16_mfma_peak": work["flops_total"] / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+                  "min_hbm_gbs": work["bytes_layer_min"] / (ms_per_step * 1e-3) / 1e9,
+                  "frac_hbm_peak": work["bytes_layer_min"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                  "phase_us": {k: v * 1e3 for k, v in phases.items()} if phases else None},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, target_s):
+    """The fp64 oracle, as it stands, on a bounded random token sample of the same workload."""
+    import oracle
+    from oracle import LayerSpec
+    spec = LayerSpec.from_workload(wl)
+    g = np.random.Generator(np.random.PCG64(99))
+
+    def run(n):
+        tok = np.sort(g.choice(wl.tokens, size=n, replace=False)).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.forward(spec, inp["x"], inp["router_w"], w13_pool, w2_pool, expert_map,
+                       logit_bias=inp["logit_bias"], shared_slots=shared, shared_range=wl.shared_range, tokens=tok)
+        return time.perf_counter() - t0
+
+    threads = oracle.max_threads()
+    n0 = min(wl.tokens, 2 * threads)
+    t_probe = run(n0)
+    n = int(max(n0, min(wl.tokens, n0 * target_s / max(t_probe, 1e-3))))
+    n = max(threads, n // threads * threads) if n < wl.tokens else wl.tokens
+    t = run(n)
+    return {"value": n / t, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {wl.tokens} tokens (random, all their local assignments), fp64, "
+                      f"{t:.1f} s wall; probe {n0} tokens {t_probe:.2f} s"}
+
+
+if __name__ == "__main__":
+    main()
