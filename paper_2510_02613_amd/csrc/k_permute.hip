@@ -107,13 +107,17 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
         const int tile_off = tile_carry + block_exclusive_scan(nt, scratch, &tile_tot);
         if (s < S) {
             p.offs[s] = row_off;
+            // split the slot's rows into nt nearly equal chunks (multiples of 32 rows, or of
+            // tile_rows when that is smaller) so that no chunk is a sliver
+            const int gran = tile_rows < 32 ? tile_rows : 32;
+            const int per = nt ? min(tile_rows, ((c + nt - 1) / nt + gran - 1) / gran * gran) : 0;
             for (int i = 0; i < nt; ++i) {
                 const int idx = tile_off + i;
                 if (idx < p.max_tiles) {
                     MTile mt;
                     mt.slot = s;
-                    mt.row_begin = row_off + i * tile_rows;
-                    mt.rows = min(tile_rows, c - i * tile_rows);
+                    mt.row_begin = row_off + i * per;
+                    mt.rows = max(0, min(per, c - i * per));
                     mt.pad = 0;
                     p.tiles[idx] = mt;
                 }

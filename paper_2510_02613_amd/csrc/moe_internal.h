@@ -59,6 +59,10 @@ hipError_t launch_permute(const Pass &p, int tile_rows, hipStream_t st);
 hipError_t launch_experts_generic(const Pass &p, int which, hipStream_t st);
 hipError_t launch_experts_mfma(const Pass &p, int which, hipStream_t st);
 int mfma_tile_rows();
+// 8-wavefront large-tile variant (needs H % 64 == 0 and I % 64 == 0)
+hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st);
+int mfma8_tile_rows();
+bool mfma8_supports(const Pass &p);
 hipError_t launch_identity_experts(const Pass &p, hipStream_t st);
 hipError_t launch_combine(const Pass &p, hipStream_t st);
 

@@ -197,3 +197,19 @@ def test_phase_timing_reports_every_phase():
         B.moe_profile_read(case.layer.handle, 3)
     B.moe_profile_enable(case.layer.handle, False)
     _full_check(case)
+
+
+@pytest.mark.parametrize("tokens", [200, 1000, 3000])
+def test_large_tile_kernels_small_shapes(tokens):
+    """Shapes whose contraction lengths are whole K-steps take the 8-wavefront kernels: groups of
+    ~50, ~250 and ~750 rows exercise partial token tiles, odd tile counts and multi-chunk groups."""
+    wl = MoEWorkload(name="big8", tokens=tokens, **{**SMALL, "inter": 128, "hidden": 320, "seed": 13})
+    _full_check(_case(wl))
+
+
+def test_large_tile_kernels_grouped_gate_shared_expert():
+    wl = MoEWorkload(name="big8g", tokens=1500, hidden=256, inter=192, n_experts=32, top_k=4,
+                     n_slots=9, n_local=8, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=4, topk_group=2, routed_scale=2.5, n_shared=1,
+                     shared_range=(100, 1317), seed=14)
+    _full_check(_case(wl))
