@@ -32,7 +32,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc runs (FETCH_SIZE and
 # WRITE_SIZE, scaled by the factor a plain copy of known size gives): bytes, or None when no
 # counter run has been recorded for that workload.  The summaries sit under profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/grouped_gemm1_qwen3_30b_a3b.md: FETCH_SIZE 526741.7 KiB x 2.000 + WRITE_SIZE 49152.0 KiB x 1.000
+    "qwen3_30b_a3b": int((526741.7 * 2.0 + 49152.0) * 1024),
+}
 
 
 def parse_args():
