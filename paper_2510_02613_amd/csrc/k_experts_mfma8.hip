@@ -8,25 +8,28 @@
 //  * Every expert's weights are used by only ~256 rows, so the layer streams all
 //    resident weights from HBM once per pass: the kernel must keep HBM busy.  A
 //    compute unit has to hold ~48 KB of weight bytes in flight to cover HBM latency
-//    at full bandwidth; the K loop therefore runs a 4-deep ring of 32 KB stages
-//    (K-step 32) and only ever waits for the OLDEST stage.
+//    at full bandwidth; the K loop therefore runs a 6-deep ring of 16 KB weight
+//    steps (K-step 32, five in flight) beside a 3-deep ring of token steps (those
+//    come from L2) and only ever waits for the OLDEST step of each.
 //  * A compute unit pulls ~64 B/clk from L2 but retires 4096 bf16 flops/clk, so a
-//    tile must reuse staged bytes >= 64 times: 256 token rows x 256 weight rows
-//    gives 128 (a 128 x 128 tile gives exactly 64 and is bandwidth bound).
+//    tile must reuse staged bytes >= 64 times: up to 320 token rows x 256 weight
+//    rows gives 114-142 (a 128 x 128 tile gives exactly 64 and is bandwidth bound).
+//    Measured, staged bytes are the scarce resource of this kernel: a group's weights
+//    should be staged once, and token rows that do not exist not at all.
 //  * Groups are ragged (tokens per expert are binomial): the tile list carries
-//    chunks of <= 256 rows balanced in units of 32, and a wavefront only multiplies
-//    the 32-row token tiles that exist.
+//    chunks of <= 320 rows balanced in units of 32 (one chunk for all but the
+//    largest groups), token rows that do not exist are neither staged nor multiplied.
 //
 // Workgroup: 8 wavefronts as 2 (token) x 4 (weight).  Wavefront (wm, wn) owns weight
-// rows [wn*64, wn*64+64) and token tiles wm, wm+2, wm+4, wm+6 (interleaved so that a
-// ragged tile count splits evenly): 2 x 4 accumulators of 32x32 = 128 registers, two
+// rows [wn*64, wn*64+64) and token tiles wm, wm+2, ... (interleaved so that a ragged
+// tile count splits evenly): up to 2 x 5 accumulators of 32x32 = 160 registers, two
 // wavefronts per SIMD so that one's LDS waits hide under the other's MFMAs.
 //
 // Staging: global_load_lds_dwordx4 -- global memory straight into LDS, 16 bytes per
 // lane, no VGPR round trip, no ds_write.  One instruction fills 16 rows x 64 bytes;
 // lane i supplies row i/4 and lands in 16-byte slot i%4, so it FETCHES chunk
-// (i%4) ^ ((row>>1)&3): the XOR swizzle that keeps the 16-byte operand reads
-// conflict free is applied on the global side.
+// (i%4) ^ swz(row): the XOR swizzle that keeps the 16-byte operand reads conflict
+// free is applied on the global side.
 //
 // GEMM-1 packs every 32-row MFMA weight tile as 16 gate rows followed by the 16
 // matching up rows; in the 32x32 accumulator layout a lane then holds gate value r
@@ -47,29 +50,45 @@ constexpr int kBK = 32;                    // K-step: 64 bytes per tile row
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
 constexpr int kBN = 256;                   // weight rows per workgroup
-constexpr int kMaxTT = 8;                  // token tiles (32 rows) per workgroup
-constexpr int kBM = kMaxTT * 32;           // 256
+constexpr int kMaxTT = 10;                 // token tiles (32 rows) per workgroup
+constexpr int kBM = kMaxTT * 32;           // 320: a whole group with its ragged tail in the usual case
 constexpr int kRows = kBN + kBM;           // LDS rows per stage
-constexpr int kStageBytes = kRows * 64;    // 32 KB
-constexpr int kStages = 4;
-constexpr int kPieces = kRows / 16;        // 1 KB pieces (16 rows) per stage = 32
-constexpr int kPiecesPerWave = kPieces / kWaves;  // 4: two weight pieces, two token pieces
+constexpr int kBKW = 64;                   // weight K-step: 128 bytes per row = one whole cache line
+constexpr int kWStage = kBN * kBKW * 2;    // 32 KB of weight rows per weight step
+constexpr int kXStage = kBM * kBK * 2;     // 16 KB of token rows per K-step
+constexpr int kNW = 3;                     // weight ring depth: 2 weight steps (64 KB) in flight from HBM
+constexpr int kNX = 3;                     // token ring depth: token rows come from L2
+constexpr int kWPieces = kWStage / 1024 / 4;   // 8: 1 KB pieces (8 rows x 128 B) per weight-loader wavefront per weight step
+constexpr int kXPieces = kXStage / 1024 / 4;   // 5: 1 KB pieces (16 rows x 64 B) per token-loader wavefront per K-step
+constexpr int kRingBytes = kNW * kWStage + kNX * kXStage;
 constexpr int kXcds = 8;
 constexpr int kTC = kMaxTT / 2;            // token tiles per wavefront
 constexpr int kWT = 2;                     // weight tiles per wavefront
 constexpr int kEpiStride1 = 2 * kWT * 16 + 8;   // GEMM-1: 32 h columns per wavefront, bytes per staged row
 constexpr int kEpiStride2 = 2 * kWT * 32 + 8;   // GEMM-2: 64 y columns per wavefront
-constexpr int kLdsBytes = (kStages * kStageBytes > kWaves * kTC * 32 * kEpiStride2) ? kStages * kStageBytes : kWaves * kTC * 32 * kEpiStride2;
-static_assert(kTC == 4, "the dispatch on token tiles per wavefront below lists cases 0..4");
+constexpr int kEpiBytes = 32 * kEpiStride2;     // one token tile of one wavefront
+constexpr int kLdsBytes = kRingBytes;
+static_assert(kWaves * kEpiBytes <= kRingBytes, "epilogue staging reuses the ring");
+static_assert(kTC == 5, "the dispatch on token tiles per wavefront below lists cases 0..5");
 static_assert(kLdsBytes <= 160 * 1024, "LDS budget");
 
 // Everything one wavefront needs for its K loop.
 struct WaveCtx {
     const uint16_t *wbase, *abase;        // slot's weight matrix, activation matrix
-    uint32_t off[kPiecesPerWave];         // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
-    uint32_t woff[kBK / 16], xoff[kBK / 16];  // LDS byte offsets (inside a stage) of this lane's operand rows per sub-step
+    uint32_t off[kWPieces];               // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
+    uint32_t woff[kBKW / 16], xoff[kBK / 16]; // LDS byte offsets (inside a stage) of this lane's operand rows per sub-step
     int wave, lane, wm, wn, n_tt;
+    int xlive;                            // token-loader wavefronts: how many of their pieces hold rows that exist
 };
+
+// 16-byte slot swizzle of a 64-byte tile row: slot = chunk ^ swz(row).  An LDS read of 16 bytes
+// per lane is served 16 lanes at a time over 64 four-byte banks (256 bytes, i.e. 4 rows): the
+// 16 consecutive rows a half-wavefront reads for one MFMA operand must therefore hit 16 distinct
+// 16-byte bank groups.  Row bits (2, 1^3) do that, and also keep any 8 consecutive rows apart on
+// a 32-bank view.
+__device__ __forceinline__ int swz(int row) { return (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1); }
+// The same for a 128-byte tile row (8 slots; 2 rows per 256 bytes): row bits (1, 2, 0^3).
+__device__ __forceinline__ int swz8(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
 
 // LDS byte address of a __shared__ object (LDS pointers are 32-bit offsets in address space 3).
 __device__ __forceinline__ uint32_t lds_addr(const void *p)
@@ -81,30 +100,43 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
 // The global address is a wave-uniform base (SGPR pair) plus this lane's 32-bit byte offset.
 // Issued as inline assembly on purpose: the compiler's wait-count insertion would otherwise
 // hold every later LDS read until these loads (which belong to a LATER stage) have returned.
-// Completion is awaited explicitly (wait_stages) before the stage's barrier.
+// Completion is awaited explicitly (wait_loads) before the step's barrier.
 __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, uint32_t lds_byte_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
-// Stage the K-step that starts at element k0 into the ring slot at stage_addr: every
-// wavefront copies its 4 pieces (w, w+8 : weight rows; w+16, w+24 : token rows).
-__device__ __forceinline__ void issue_stage(const WaveCtx &c, uint32_t stage_addr, int k0)
+// Loader roles: wavefronts 0-3 stream the weight rows, wavefronts 4-7 the token rows, 4 pieces
+// each per K-step.  The split matters because a wavefront's loads complete in order: a single
+// wavefront issuing both could not keep five weight steps in flight while waiting for the much
+// younger token step.
+__device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
-    const uint16_t *wb = c.wbase + k0, *ab = c.abase + k0;
+    if (c.wave < 4) {
+        const uint16_t *b = c.wbase + k0;
 #pragma unroll
-    for (int i = 0; i < kPiecesPerWave; ++i) {
-        const int pb = c.wave + i * kWaves;
-        dma_piece(i < kPiecesPerWave / 2 ? wb : ab, c.off[i], stage_addr + pb * 1024);
+        for (int i = 0; i < kWPieces; ++i) dma_piece(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
+    } else {
+        const uint16_t *b = c.abase + k0;
+#pragma unroll
+        for (int i = 0; i < kXPieces; ++i)
+            if (i < c.xlive) dma_piece(b, c.off[i], slot_addr + ((c.wave & 3) + 4 * i) * 1024);
     }
 }
 
-// Wait until at most `pending` of this wavefront's staged K-steps are still in flight.
-template <int pending>
-__device__ __forceinline__ void wait_stages()
+// Orders this wavefront's own LDS traffic (writes before, reads after).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Wait until at most n of this wavefront's loads are still in flight (they complete in order).
+template <int n>
+__device__ __forceinline__ void wait_loads()
 {
     // s_waitcnt simm16: vmcnt = bits [3:0] and [15:14], expcnt [6:4] = 7, lgkmcnt [11:8] = 15 (no wait)
-    constexpr int n = pending * kPiecesPerWave;
     static_assert(n < 64, "vmcnt has 6 bits");
     __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8));
 }
@@ -113,16 +145,16 @@ __device__ __forceinline__ void wait_stages()
 // (sub-step, token tile) pairs run as one software pipeline: the token operand of pair s+2 and
 // the weight operands of the next sub-step are requested from LDS before the MFMAs of pair s.
 template <int NTC>
-__device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *stage, f32x16 (&acc)[kWT][kTC])
+__device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws, const char *Xs, int half, f32x16 (&acc)[kWT][kTC])
 {
     if constexpr (NTC > 0) {
-        const char *Ws = stage, *Xs = stage + kBN * 64;
         constexpr int KS = kBK / 16, STEPS = KS * NTC, D = 2;
         bf16x8 wf[2][kWT], xf[D + 1];
+        const uint32_t w0 = half ? c.woff[2] : c.woff[0], w1 = half ? c.woff[3] : c.woff[1];  // this half's two sub-steps
         auto fetch_w = [&](int ks) {
 #pragma unroll
             for (int a = 0; a < kWT; ++a) {
-                const uint4 v = *(const uint4 *)(Ws + c.woff[ks] + a * 32 * 64);
+                const uint4 v = *(const uint4 *)(Ws + (ks ? w1 : w0) + a * 32 * 128);
                 wf[ks & 1][a] = *(const bf16x8 *)&v;
             }
         };
@@ -150,15 +182,42 @@ __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *sta
 template <int NTC>
 __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int KT, f32x16 (&acc)[kWT][kTC])
 {
-    const uint32_t a0 = lds_addr(ring);
-    // the caller issued stages 0 .. kStages-2 (those that exist)
+    // KT K-steps of 32; weight steps cover two of them.  The caller issued weight steps 0, 1 and
+    // token steps 0, 1 (those that exist).
+    const bool wloader = c.wave < 4;
+    const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
+    const int WT_ = KT / 2;                                    // weight steps
+    int wslot = 0, xslot = 0, wfill = kNW - 1, xfill = kNX - 1;
     for (int kt = 0; kt < KT; ++kt) {
-        // stage kt must have landed: allow the kStages-2 younger ones to stay in flight
-        if (kt + kStages - 2 < KT) wait_stages<kStages - 2>();
-        else                       wait_stages<0>();
-        __syncthreads();  // everyone's share of stage kt is in LDS; everyone is done reading stage kt-1
-        if (kt + kStages - 1 < KT) issue_stage(c, a0 + ((kt + kStages - 1) % kStages) * kStageBytes, (kt + kStages - 1) * kBK);
-        multiply_stage<NTC>(c, ring + (kt % kStages) * kStageBytes, acc);
+        const int half = kt & 1, ws = kt >> 1;
+        // this wavefront's share of what step kt reads must have landed; younger steps stay in flight
+        if (wloader) {
+            if (!half) { if (ws + 1 < WT_) wait_loads<kWPieces>(); else wait_loads<0>(); }
+        } else {
+            if (kt + 1 < KT) {   // one younger token step (xlive loads) may stay in flight
+                switch (c.xlive) {
+                case 5: wait_loads<5>(); break;
+                case 4: wait_loads<4>(); break;
+                case 3: wait_loads<3>(); break;
+                case 2: wait_loads<2>(); break;
+                case 1: wait_loads<1>(); break;
+                default: wait_loads<0>(); break;
+                }
+            } else {
+                wait_loads<0>();
+            }
+        }
+        __syncthreads();  // everyone's share of step kt is in LDS; everyone is done reading step kt-1
+        if (wloader) {
+            if (!half && ws + kNW - 1 < WT_) issue_step(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
+        } else {
+            if (kt + kNX - 1 < KT) issue_step(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
+        }
+        multiply_stage<NTC>(c, ring + wslot * kWStage, ring + kNW * kWStage + xslot * kXStage, half, acc);
+        if (half) { wslot = wslot + 1 == kNW ? 0 : wslot + 1; }
+        else      { wfill = wfill + 1 == kNW ? 0 : wfill + 1; }
+        xslot = xslot + 1 == kNX ? 0 : xslot + 1;
+        xfill = xfill + 1 == kNX ? 0 : xfill + 1;
     }
 }
 
@@ -178,11 +237,16 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
     // ---- epilogue: accumulators -> private LDS region [token row][column] -> coalesced rows ----
     constexpr int COLS = kFirst ? kWT * 16 : kWT * 32;      // output columns of this wavefront
     constexpr int STRIDE = kFirst ? kEpiStride1 : kEpiStride2;
-    char *mine = ring + c.wave * (kTC * 32 * kEpiStride2);
+    char *mine = ring + c.wave * kEpiBytes;
     const int l31 = c.lane & 31, khalf = c.lane >> 5;
+    constexpr int LPR = COLS / 4;                           // copy out: 8 bytes per lane, LPR lanes per row,
+    constexpr int RPI = 64 / LPR;                           // 64/LPR rows per instruction
+    uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y);
+    const int ncol0 = n0 + c.wn * COLS;
+    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
 #pragma unroll
     for (int t = 0; t < NTC; ++t) {
-        char *row = mine + (t * 32 + l31) * STRIDE;
+        char *row = mine + l31 * STRIDE;
 #pragma unroll
         for (int a = 0; a < kWT; ++a) {
             constexpr int Q = kFirst ? 2 : 4;
@@ -202,26 +266,16 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
                 *(uint2 *)(row + col * 2) = make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
             }
         }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // copy out: 8 bytes per lane, LPR lanes per row, 64/LPR rows per instruction
-    constexpr int LPR = COLS / 4;
-    constexpr int RPI = 64 / LPR;
-    uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y);
-    const int ncol0 = n0 + c.wn * COLS;
-    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
-#pragma unroll
-    for (int t = 0; t < NTC; ++t) {
+        wave_lds_sync();
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += RPI) {
             const int rr = r0 + lr;                       // row inside the token tile
             const int m = (2 * t + c.wm) * 32 + rr;       // row inside the chunk
-            const uint2 v = *(const uint2 *)(mine + (t * 32 + rr) * STRIDE + lc * 2);
+            const uint2 v = *(const uint2 *)(mine + rr * STRIDE + lc * 2);
             if (m < mt.rows && ncol0 + lc < N)
                 *(uint2 *)(O + (size_t)(mt.row_begin + m) * N + ncol0 + lc) = v;
         }
+        wave_lds_sync();  // the region is rewritten by the next token tile
     }
 }
 
@@ -249,18 +303,20 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     c.wn = c.wave & 3;
     c.wm = c.wave >> 2;
     c.n_tt = (mt.rows + 31) >> 5;                      // token tiles that exist
+    c.xlive = c.wave < 4 ? 0 : min(kXPieces, max(0, (2 * c.n_tt - (c.wave & 3) + 3) >> 2));  // pieces w, w+4, ... < 2*n_tt
 
     // ---- staging plan ----
     const uint16_t *W = (const uint16_t *)(kFirst ? p.w13 : p.w2) + (size_t)mt.slot * (kFirst ? 2 : 1) * (size_t)p.I * p.H;
     const uint16_t *A = (const uint16_t *)(kFirst ? p.x : p.h);
     c.wbase = W;
     c.abase = A;
+    if (c.wave < 4) {
 #pragma unroll
-    for (int i = 0; i < kPiecesPerWave; ++i) {
-        const int pb = c.wave + i * kWaves;            // piece: LDS rows pb*16 .. +16 of the stage
-        const int row = pb * 16 + (c.lane >> 2);
-        const int chunk = (c.lane & 3) ^ ((row >> 1) & 3);
-        if (i < kPiecesPerWave / 2) {                  // weight rows
+        for (int i = 0; i < kWPieces; ++i) {
+            // weight piece: rows [8*pc, 8*pc+8) of the weight tile, 128 bytes each
+            const int pc = c.wave * kWPieces + i;
+            const int row = pc * 8 + (c.lane >> 3);
+            const int chunk = (c.lane & 7) ^ swz8(row);
             int g;
             if (kFirst) {
                 const int tile = row >> 5, within = row & 31;
@@ -270,32 +326,39 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
                 g = min(n0 + row, N - 1);
             }
             c.off[i] = ((uint32_t)g * K + chunk * 8) * 2;
-        } else {                                       // token rows (rows past the chunk re-read its last row)
-            const int r = min(row - kBN, mt.rows - 1);
-            const int s = kFirst ? p.perm[mt.row_begin + r] : mt.row_begin + r;
-            c.off[i] = ((uint32_t)s * K + chunk * 8) * 2;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kXPieces; ++i) {
+            // token piece: rows [16*pc, 16*pc+16) of the token tile, 64 bytes each (rows past the chunk re-read its last row)
+            const int pc = (c.wave & 3) + 4 * i;   // interleaved over the 4 loaders so that live pieces are shared evenly
+            const int row = pc * 16 + (c.lane >> 2);
+            const int chunk = (c.lane & 3) ^ swz(row);
+            const int r = min(row, mt.rows - 1);
+            const int sr = kFirst ? p.perm[mt.row_begin + r] : mt.row_begin + r;
+            c.off[i] = ((uint32_t)sr * K + chunk * 8) * 2;
         }
     }
     {   // operand rows of this lane: weight row wn*64 + l31 (+32a), token row wm*32 + l31 (+64t)
         const int l31 = c.lane & 31, khalf = c.lane >> 5;
+        const int wr = c.wn * kWT * 32 + l31, xr = c.wm * 32 + l31;
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            const int chunk = ks * 2 + khalf;
-            const int wr = c.wn * kWT * 32 + l31, xr = c.wm * 32 + l31;
-            c.woff[ks] = wr * 64 + ((chunk ^ ((wr >> 1) & 3)) << 4);
-            c.xoff[ks] = xr * 64 + ((chunk ^ ((xr >> 1) & 3)) << 4);
-        }
+        for (int ks = 0; ks < kBKW / 16; ++ks) c.woff[ks] = wr * 128 + (((ks * 2 + khalf) ^ swz8(wr)) << 4);
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) c.xoff[ks] = xr * 64 + (((ks * 2 + khalf) ^ swz(xr)) << 4);
     }
 
     const int KT = K / kBK;
-    const uint32_t a0 = lds_addr(ring);
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-        if (s < KT) issue_stage(c, a0 + s * kStageBytes, s * kBK);
+    {
+        const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
+        if (c.wave < 4) { for (int s = 0; s < kNW - 1 && s < KT / 2; ++s) issue_step(c, wring + s * kWStage, s * kBKW); }
+        else            { for (int s = 0; s < kNX - 1 && s < KT; ++s) issue_step(c, xring + s * kXStage, s * kBK); }
+    }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
     const int ntc = (c.n_tt - c.wm + 1) >> 1;
     switch (ntc) {
+    case 5: wave_body<kFirst, 5>(p, c, mt, n0, N, KT, ring); break;
     case 4: wave_body<kFirst, 4>(p, c, mt, n0, N, KT, ring); break;
     case 3: wave_body<kFirst, 3>(p, c, mt, n0, N, KT, ring); break;
     case 2: wave_body<kFirst, 2>(p, c, mt, n0, N, KT, ring); break;
@@ -309,7 +372,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
 int mfma8_tile_rows() { return kBM; }
 
 // usable when both contraction lengths are whole K-steps (direct-to-LDS loads cannot zero fill)
-bool mfma8_supports(const Pass &p) { return p.act_bf16 && p.H % kBK == 0 && p.I % kBK == 0; }
+bool mfma8_supports(const Pass &p) { return p.act_bf16 && p.H % kBKW == 0 && p.I % kBKW == 0; }
 
 hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st)
 {

@@ -197,165 +197,209 @@ __global__ __launch_bounds__(kThreads) void k_gate(Pass p)
 
 
 // ---------------------------------------------------------------------------------
-// Matrix-core variant for bf16 activations.
+// Matrix-core path for bf16 activations: a logits kernel and a selection kernel.
 //
-// A workgroup owns 16*TBT tokens; each of its 4 wavefronts owns every 4th tile of 16
-// experts.  Both MFMA operands are read straight from global memory in operand
-// layout (no LDS): for a K-chunk of 128, lane (n = l%16, q = l/16) reads 32 of the
-// 128 k of row n, interleaved with the other three lanes of the row in units of 8,
-// and feeds them to the matrix core 8 (bf16) or 1 (fp32) at a time.  The
-// contraction does not care which k a lane group carries as long as the router row
-// and the token row use the same assignment, which they do.
+// k_gate_logits.  A workgroup owns 16*TT tokens x a block of experts and writes their
+// fp32 logits to the workspace.  Both MFMA operands are read straight from global
+// memory in operand layout (no LDS): for a K-chunk of 128, lane (n = l%16, q = l/16)
+// reads 32 of the 128 k of row n, interleaved with the other three lanes of the row
+// in units of 8, and feeds them to the matrix core 8 (bf16) or 1 (fp32) at a time.
+// The contraction does not care which k a lane group carries as long as the router
+// row and the token row use the same assignment, which they do.
 //   bf16 router: v_mfma_f32_16x16x32_bf16, fp32 accumulate.
 //   fp32 router: tokens widened to fp32 (exact), v_mfma_f32_16x16x4_f32: every
-//                product is a true fp32 product, as the "fp32 gate" of the Qwen3-
-//                shaped workload requires.
+//                product is a true fp32 product ("fp32 gate").
 // The next chunk's loads are issued before the current chunk's MFMAs.
+// Two ways to split a workgroup's work over its 4 wavefronts:
+//   expert split (KSPLIT = false): wavefront w owns ET expert tiles of the workgroup's
+//       4*ET tiles; used when there are enough tokens to fill the chip;
+//   K split (KSPLIT = true): all wavefronts own the same ET expert tiles and a quarter
+//       of K each; partial sums meet in LDS and are added in wavefront order
+//       (deterministic).  Used for decode-sized batches, where the router matrix
+//       must be streamed by many workgroups at once.
+//
+// k_gate_select.  One wavefront per token: scores, group limiting, top-k, weights
+// (select_token above).  Its reductions are latency chains, so it runs as many small
+// workgroups as possible and lets occupancy hide them.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <typename WT> struct RouterRun;           // the lane's 32 k of one router row
+template <typename WT> struct RouterRun;           // the lane's 32 k of one row
 template <> struct RouterRun<uint16_t> { uint4 v[4]; };
 template <> struct RouterRun<float> { uint4 v[8]; };
 
 // Loads the lane's 32 elements of a 128-wide K chunk.  Element (jj, i) of the lane in k-group q
 // is k0 + jj*32 + q*8 + i (jj < 4, i < 8): the four lanes of a row then read one contiguous
-// 64-byte (bf16) or 128-byte (fp32) span per pair of load instructions, instead of 64 scattered
-// lines per instruction.
+// 64-byte (bf16) or 128-byte (fp32) span per pair of load instructions.
 template <typename WT>
-__device__ __forceinline__ void load_run(RouterRun<WT> &r, const WT *row, int k0, int q, int H)
+__device__ __forceinline__ void load_run(RouterRun<WT> &r, const WT *row, int k0, int q, int kend)
 {
     constexpr int per16 = 16 / sizeof(WT);  // elements per 16-byte load: 8 or 4
     constexpr int parts = 8 / per16;         // loads per 8 elements: 1 or 2
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
         const int k = k0 + jj * 32 + q * 8;
-        const bool ok = k < H;  // H % 8 == 0: the 8 elements are all in or all out
+        const bool ok = k < kend;  // kend % 8 == 0: the 8 elements are all in or all out
 #pragma unroll
         for (int h = 0; h < parts; ++h)
             r.v[jj * parts + h] = ok ? *(const uint4 *)(row + k + h * per16) : make_uint4(0, 0, 0, 0);
     }
 }
 
-template <typename WT, int TBT, int GT>
-__global__ __launch_bounds__(kThreads) void k_gate_mfma(Pass p)
+template <typename WT, int TT, int ET, bool KSPLIT>
+__global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
 {
-    extern __shared__ float smem[];
+    __shared__ float part[KSPLIT ? 4 * TT * ET * 256 : 1];
     const int E = p.E, H = p.H;
-    float *lg = smem;                     // [16*TBT][E]
-    float *cs = lg + 16 * TBT * E;        // [4 waves][E]
-    float *gsc = cs + 4 * E;              // [4 waves][64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, q = lane >> 4;
-    const int t0 = blockIdx.x * 16 * TBT;
-    const int n_etiles = (E + 15) / 16;
+    const int t0 = blockIdx.x * 16 * TT;
+    const int et0 = KSPLIT ? blockIdx.y * ET : (blockIdx.y * 4 + wave) * ET;   // first expert tile of this wavefront
+    if (!KSPLIT && et0 * 16 >= E) return;
     const uint16_t *x = (const uint16_t *)p.x;
     const WT *wr = (const WT *)p.router_w;
+    // K range of this wavefront (whole chunks of 128)
+    int kbeg = 0, kend = H;
+    if (KSPLIT) {
+        const int chunks = (H + 127) / 128, per = (chunks + 3) / 4;
+        kbeg = min(H, wave * per * 128);
+        kend = min(H, (wave + 1) * per * 128);
+    }
 
-    const uint16_t *xrow[TBT];
+    const uint16_t *xrow[TT];
+    const WT *wrow[ET];
 #pragma unroll
-    for (int tb = 0; tb < TBT; ++tb) xrow[tb] = x + (size_t)min(t0 + tb * 16 + n, p.T - 1) * H;
+    for (int tb = 0; tb < TT; ++tb) xrow[tb] = x + (size_t)min(t0 + tb * 16 + n, p.T - 1) * H;
+#pragma unroll
+    for (int a = 0; a < ET; ++a) wrow[a] = wr + (size_t)min((et0 + a) * 16 + n, E - 1) * H;
 
-    for (int g0 = 0; g0 < n_etiles; g0 += 4 * GT) {
-        // this wavefront's expert tiles in the sweep: g0 + wave + 4a
-        int n_act = 0;
-        const WT *wrow[GT];
+    f32x4 acc[ET][TT];
 #pragma unroll
-        for (int a = 0; a < GT; ++a) {
-            const int et = g0 + wave + 4 * a;
-            if (et < n_etiles) n_act = a + 1;
-            wrow[a] = wr + (size_t)min(et * 16 + n, E - 1) * H;
-        }
-        f32x4 acc[GT][TBT];
+    for (int a = 0; a < ET; ++a)
 #pragma unroll
-        for (int a = 0; a < GT; ++a)
-#pragma unroll
-            for (int tb = 0; tb < TBT; ++tb) acc[a][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int tb = 0; tb < TT; ++tb) acc[a][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-        RouterRun<uint16_t> xc[TBT], xn[TBT];
-        RouterRun<WT> wc[GT], wn[GT];
-        auto load_chunk = [&](int k0, RouterRun<uint16_t> *xd, RouterRun<WT> *wd) {
+    RouterRun<uint16_t> xc[TT], xn[TT];
+    RouterRun<WT> wc[ET], wn[ET];
+    auto load_chunk = [&](int k0, RouterRun<uint16_t> *xd, RouterRun<WT> *wd) {
 #pragma unroll
-            for (int tb = 0; tb < TBT; ++tb) load_run<uint16_t>(xd[tb], xrow[tb], k0, q, H);
+        for (int tb = 0; tb < TT; ++tb) load_run<uint16_t>(xd[tb], xrow[tb], k0, q, kend);
 #pragma unroll
-            for (int a = 0; a < GT; ++a)
-                if (a < n_act) load_run<WT>(wd[a], wrow[a], k0, q, H);
-        };
-        load_chunk(0, xc, wc);
-        for (int k0 = 0; k0 < H; k0 += 128) {
-            if (k0 + 128 < H) load_chunk(k0 + 128, xn, wn);
-            if constexpr (sizeof(WT) == 2) {
+        for (int a = 0; a < ET; ++a) load_run<WT>(wd[a], wrow[a], k0, q, kend);
+    };
+    if (kbeg < kend) load_chunk(kbeg, xc, wc);
+    for (int k0 = kbeg; k0 < kend; k0 += 128) {
+        if (k0 + 128 < kend) load_chunk(k0 + 128, xn, wn);
+        if constexpr (sizeof(WT) == 2) {
 #pragma unroll
-                for (int a = 0; a < GT; ++a)
-                    if (a < n_act) {
+            for (int a = 0; a < ET; ++a)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
-                            for (int tb = 0; tb < TBT; ++tb)
-                                acc[a][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&wc[a].v[j], *(bf16x8 *)&xc[tb].v[j], acc[a][tb], 0, 0, 0);
-                    }
-            } else {
-                float xf[TBT][32];
+                    for (int tb = 0; tb < TT; ++tb)
+                        acc[a][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&wc[a].v[j], *(bf16x8 *)&xc[tb].v[j], acc[a][tb], 0, 0, 0);
+        } else {
+            float xf[TT][32];
 #pragma unroll
-                for (int tb = 0; tb < TBT; ++tb)
+            for (int tb = 0; tb < TT; ++tb)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint32_t *u = (const uint32_t *)&xc[tb].v[j];
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t *u = (const uint32_t *)&xc[tb].v[j];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            xf[tb][j * 8 + 2 * e] = __uint_as_float(u[e] << 16);
-                            xf[tb][j * 8 + 2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
-                        }
-                    }
-#pragma unroll
-                for (int a = 0; a < GT; ++a)
-                    if (a < n_act) {
-                        const float *wf = (const float *)&wc[a].v[0];
-#pragma unroll
-                        for (int e = 0; e < 32; ++e)
-#pragma unroll
-                            for (int tb = 0; tb < TBT; ++tb)
-                                acc[a][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[e], xf[tb][e], acc[a][tb], 0, 0, 0);
-                    }
-            }
-#pragma unroll
-            for (int tb = 0; tb < TBT; ++tb) xc[tb] = xn[tb];
-#pragma unroll
-            for (int a = 0; a < GT; ++a) wc[a] = wn[a];
-        }
-        // lane holds token n of each token tile, experts 4q + r of each of its expert tiles
-#pragma unroll
-        for (int a = 0; a < GT; ++a)
-            if (a < n_act) {
-                const int et = g0 + wave + 4 * a;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = et * 16 + 4 * q + r;
-                    if (e < E) {
-                        const float b = p.logit_bias ? p.logit_bias[e] : 0.f;
-#pragma unroll
-                        for (int tb = 0; tb < TBT; ++tb) lg[(tb * 16 + n) * E + e] = acc[a][tb][r] + b;
+                    for (int e = 0; e < 4; ++e) {
+                        xf[tb][j * 8 + 2 * e] = __uint_as_float(u[e] << 16);
+                        xf[tb][j * 8 + 2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
                     }
                 }
+#pragma unroll
+            for (int a = 0; a < ET; ++a) {
+                const float *wf = (const float *)&wc[a].v[0];
+#pragma unroll
+                for (int e = 0; e < 32; ++e)
+#pragma unroll
+                    for (int tb = 0; tb < TT; ++tb)
+                        acc[a][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[e], xf[tb][e], acc[a][tb], 0, 0, 0);
             }
+        }
+#pragma unroll
+        for (int tb = 0; tb < TT; ++tb) xc[tb] = xn[tb];
+#pragma unroll
+        for (int a = 0; a < ET; ++a) wc[a] = wn[a];
     }
-    __syncthreads();
-    for (int tt = wave; tt < 16 * TBT; tt += 4) {
-        const int t = t0 + tt;
-        if (t < p.T) select_token(p, t, lg + tt * E, cs + wave * E, gsc + wave * 64, lane);
+
+    if (KSPLIT) {  // partial sums of the 4 K-quarters meet in LDS, added in wavefront order
+#pragma unroll
+        for (int a = 0; a < ET; ++a)
+#pragma unroll
+            for (int tb = 0; tb < TT; ++tb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) part[((wave * ET + a) * TT + tb) * 256 + r * 64 + lane] = acc[a][tb][r];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int a = 0; a < ET; ++a)
+#pragma unroll
+            for (int tb = 0; tb < TT; ++tb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) s += part[((w * ET + a) * TT + tb) * 256 + r * 64 + lane];
+                    acc[a][tb][r] = s;
+                }
     }
+    // lane holds token n of each token tile, experts 4q + r of each of its expert tiles
+#pragma unroll
+    for (int a = 0; a < ET; ++a)
+#pragma unroll
+        for (int tb = 0; tb < TT; ++tb) {
+            const int t = t0 + tb * 16 + n;
+            const int e = (et0 + a) * 16 + 4 * q;   // E may be any size: guard each of the 4
+            if (t < p.T) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (e + r < E) p.logits[(size_t)t * E + e + r] = acc[a][tb][r] + (p.logit_bias ? p.logit_bias[e + r] : 0.f);
+            }
+        }
 }
 
-template <typename WT, int TBT, int GT>
-hipError_t launch_gate_mfma_t(const Pass &p, hipStream_t st)
+__global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
 {
-    const int blocks = (p.T + 16 * TBT - 1) / (16 * TBT);
-    const size_t smem = sizeof(float) * ((size_t)16 * TBT * p.E + 4 * (size_t)p.E + 4 * 64);
-    if (smem > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gate_mfma<WT, TBT, GT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((k_gate_mfma<WT, TBT, GT>), dim3(blocks), dim3(kThreads), smem, st, p);
+    extern __shared__ float smem[];
+    const int E = p.E;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *lg = smem + wave * (2 * E + 64);   // [E] logits -> scores
+    float *cs = lg + E;                       // [E] selection scores
+    float *gsc = cs + E;                      // [64]
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= p.T) return;
+    for (int e = lane; e < E; e += 64) lg[e] = p.logits[(size_t)t * E + e];
+    wave_sync();
+    select_token(p, t, lg, cs, gsc, lane);
+}
+
+template <typename WT, int TT, int ET, bool KSPLIT>
+hipError_t launch_gate_logits_t(const Pass &p, hipStream_t st)
+{
+    const int eb = (KSPLIT ? 1 : 4) * ET * 16;
+    dim3 grid((p.T + 16 * TT - 1) / (16 * TT), (p.E + eb - 1) / eb);
+    hipLaunchKernelGGL((k_gate_logits<WT, TT, ET, KSPLIT>), grid, dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
+template <typename WT>
+hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
+{
+    // pick the split that gives the chip enough workgroups
+    auto blocks = [&](int tt, int et) { return ((p.T + 16 * tt - 1) / (16 * tt)) * ((p.E + 64 * et - 1) / (64 * et)); };
+    hipError_t e;
+    if (p.T <= 256)                                   e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
+    else if (sizeof(WT) == 2 && blocks(4, 2) >= 192)  e = launch_gate_logits_t<WT, 4, 2, false>(p, st);
+    else if (blocks(2, 1) >= 192)                     e = launch_gate_logits_t<WT, 2, 1, false>(p, st);
+    else                                              e = launch_gate_logits_t<WT, 1, 1, false>(p, st);
+    if (e != hipSuccess) return e;
+    const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);
+    hipLaunchKernelGGL(k_gate_select, dim3((p.T + 3) / 4), dim3(kThreads), smem, st, p);
     return hipGetLastError();
 }
 
@@ -363,13 +407,7 @@ hipError_t launch_gate_mfma_t(const Pass &p, hipStream_t st)
 
 hipError_t launch_gate(const Pass &p, hipStream_t st)
 {
-    if (p.act_bf16) {
-        // token tiles per workgroup: enough workgroups to cover the chip first, then fewer sweeps
-        // of the router matrix through L2 (each workgroup reads all of it)
-        const bool two = p.T >= 2 * 16 * 256;
-        if (p.router_bf16) return two ? launch_gate_mfma_t<uint16_t, 2, 4>(p, st) : launch_gate_mfma_t<uint16_t, 1, 4>(p, st);
-        return two ? launch_gate_mfma_t<float, 2, 2>(p, st) : launch_gate_mfma_t<float, 1, 2>(p, st);
-    }
+    if (p.act_bf16) return p.router_bf16 ? launch_gate_mfma<uint16_t>(p, st) : launch_gate_mfma<float>(p, st);
     const int blocks = (p.T + kTokens - 1) / kTokens;
     const size_t smem = sizeof(float) * (kTokens * kKC + kET * (kKC + 1) + (size_t)kTokens * p.E + 4 * (size_t)p.E + 4 * 64);
     dim3 grid(blocks), block(kThreads);

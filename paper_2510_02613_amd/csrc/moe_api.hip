@@ -34,7 +34,7 @@ constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: siz
 
 // Offsets of every intermediate inside the workspace.
 struct Layout {
-    size_t map[2], ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, total;
+    size_t map[2], logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, total;
 };
 
 size_t esize(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
@@ -79,6 +79,7 @@ Layout make_layout(const moe_config_t &c)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     L.map[0] = take(4 * (c.n_experts + c.n_shared));
     L.map[1] = take(4 * (c.n_experts + c.n_shared));
+    L.logits = take(c.act_dtype == MOE_BF16 ? 4 * T * c.n_experts : 0);
     L.ids = take(4 * T * k);
     L.w = take(4 * T * k);
     L.slot_rank = take(4 * A);
@@ -278,6 +279,7 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     p.router_w = l->buf.router_w; p.logit_bias = l->buf.logit_bias; p.select_bias = l->buf.select_bias;
     p.w13 = l->buf.w13; p.w2 = l->buf.w2;
     p.map = (const int32_t *)(ws + l->lay.map[l->active]);
+    p.logits = (float *)(ws + l->lay.logits);
     p.ids = (int32_t *)(ws + l->lay.ids);
     p.w = (float *)(ws + l->lay.w);
     p.slot_rank = (int32_t *)(ws + l->lay.slot_rank);

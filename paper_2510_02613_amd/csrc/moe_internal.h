@@ -35,6 +35,7 @@ struct Pass {
     const void *w13, *w2;
     // workspace
     const int32_t *map;  // [E + n_shared] active table, shared slots last
+    float *logits;       // [T,E] gate logits (bf16-activation path)
     int32_t *ids;        // [T,k]
     float *w;            // [T,k]
     int32_t *slot_rank;  // [T*kk] (slot << 12 | rank-in-block) or -1
