@@ -297,7 +297,9 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     const bool mfma = p.act_bf16 && !(flags & MOE_FLAG_FORCE_GENERIC);
     // large tiles once groups average at least a few MFMA tiles of rows
     const bool big = mfma && mfma8_supports(p) && (long long)T * p.kk >= 48ll * p.S;
-    const int tile_rows = big ? mfma8_tile_rows() : mfma ? mfma_tile_rows() : kGenericTileRows;
+    // weight streaming when a slot expects only a handful of rows (routed: T*k/E on average)
+    const bool tiny = mfma && !big && (long long)T * p.k <= 4ll * p.E && shared_end - shared_begin <= 2 * decode_tile_rows();
+    const int tile_rows = big ? mfma8_tile_rows() : tiny ? decode_tile_rows() : mfma ? mfma_tile_rows() : kGenericTileRows;
     p.max_tiles = (int)(((long long)T * p.kk + tile_rows - 1) / tile_rows) + p.S;
 
     // optional phase events (benchmarks): event j is recorded before phase j, the last one after the pass
@@ -312,12 +314,13 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     if (e == hipSuccess) {
         if (identity)  e = launch_identity_experts(p, st);
         else if (big)  e = launch_experts_mfma8(p, 0, st);
+        else if (tiny) e = launch_experts_decode(p, 0, st);
         else if (mfma) e = launch_experts_mfma(p, 0, st);
         else           e = launch_experts_generic(p, 0, st);
     }
     mark(MOE_PHASE_GEMM2);
     if (e == hipSuccess && !identity)
-        e = big ? launch_experts_mfma8(p, 1, st) : mfma ? launch_experts_mfma(p, 1, st) : launch_experts_generic(p, 1, st);
+        e = big ? launch_experts_mfma8(p, 1, st) : tiny ? launch_experts_decode(p, 1, st) : mfma ? launch_experts_mfma(p, 1, st) : launch_experts_generic(p, 1, st);
     mark(MOE_PHASE_COMBINE);
     if (e == hipSuccess) e = launch_combine(p, st);
     mark(MOE_N_PHASES);

@@ -64,6 +64,9 @@ int mfma_tile_rows();
 hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st);
 int mfma8_tile_rows();
 bool mfma8_supports(const Pass &p);
+// weight-streaming variant for decode-sized batches (M-tiles of 16 rows)
+hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st);
+int decode_tile_rows();
 hipError_t launch_identity_experts(const Pass &p, hipStream_t st);
 hipError_t launch_combine(const Pass &p, hipStream_t st);
 

@@ -213,3 +213,17 @@ def test_large_tile_kernels_grouped_gate_shared_expert():
                      gate="sigmoid_group", n_group=4, topk_group=2, routed_scale=2.5, n_shared=1,
                      shared_range=(100, 1317), seed=14)
     _full_check(_case(wl))
+
+
+@pytest.mark.parametrize("tokens", [3, 24])
+def test_weight_streaming_kernels_small_shapes(tokens):
+    """Decode-sized batches take the weight-streaming expert kernels: ragged K (264, 136 are not
+    multiples of the 128-wide K chunk), a shared expert whose rows span two 16-row tiles, slots
+    with no rows at all."""
+    wl = MoEWorkload(name="decode_small", tokens=tokens, hidden=264, inter=136, n_experts=32, top_k=4,
+                     n_slots=17, n_local=16, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=4, topk_group=2, routed_scale=2.5, n_shared=1,
+                     shared_range=(min(2, tokens), min(22, tokens)), seed=15)
+    case = _case(wl)
+    _, v, _ = _full_check(case)
+    assert (v["counts"] == 0).any()
