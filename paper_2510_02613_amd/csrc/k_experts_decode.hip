@@ -77,6 +77,7 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
             load_run(nb, wb, k0 + 128, q, K);
             load_run(nx, xr, k0 + 128, q, K);
         }
+        __builtin_amdgcn_sched_barrier(0);  // the prefetch must be issued before this chunk's MFMAs, not after
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             acc_a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&ca.v[jj], *(bf16x8 *)&cx.v[jj], acc_a, 0, 0, 0);

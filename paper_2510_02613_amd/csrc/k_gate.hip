@@ -36,20 +36,43 @@ __device__ __forceinline__ unsigned long long make_key(float score, int idx)
 }
 __device__ __forceinline__ int key_index(unsigned long long key) { return (int)(0xffffffffu - (uint32_t)(key & 0xffffffffull)); }
 
+// Wavefront reductions on the DPP network (no LDS round trips): row_shr 1,2,4,8 leave each row's
+// result in its lane 15, row_bcast15 / row_bcast31 carry it across rows, lane 63 ends up with the
+// whole wavefront's result, which is then read back as a scalar.  Lanes without a source take the
+// operation's identity.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i32(int identity, int v)
+{
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+#define EMOE_DPP_REDUCE(STEP)                                                             \
+    STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) /* row_shr 1,2,4,8 */ \
+    STEP(0x142, 0xa) STEP(0x143, 0xc)                                   /* row_bcast15, 31 */
+
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        unsigned long long o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
+    unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
+#define STEP(CTRL, MASK)                                                                   \
+    {                                                                                      \
+        const unsigned ohi = (unsigned)dpp_i32<CTRL, MASK>(0, (int)hi);                    \
+        const unsigned olo = (unsigned)dpp_i32<CTRL, MASK>(0, (int)lo);                    \
+        const bool take = ohi > hi || (ohi == hi && olo > lo);                             \
+        hi = take ? ohi : hi;                                                              \
+        lo = take ? olo : lo;                                                              \
     }
-    return v;
+    EMOE_DPP_REDUCE(STEP)
+#undef STEP
+    hi = (unsigned)__builtin_amdgcn_readlane((int)hi, 63);
+    lo = (unsigned)__builtin_amdgcn_readlane((int)lo, 63);
+    return ((unsigned long long)hi << 32) | lo;
 }
 __device__ __forceinline__ float wave_max_f32(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    const int ninf = (int)0xff800000u;
+#define STEP(CTRL, MASK) v = fmaxf(v, __int_as_float(dpp_i32<CTRL, MASK>(ninf, __float_as_int(v))));
+    EMOE_DPP_REDUCE(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 // Orders this wavefront's LDS traffic: writes before it are visible to every lane after it.
 __device__ __forceinline__ void wave_sync()
@@ -60,9 +83,10 @@ __device__ __forceinline__ void wave_sync()
 }
 __device__ __forceinline__ float wave_sum_f32(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+#define STEP(CTRL, MASK) v += __int_as_float(dpp_i32<CTRL, MASK>(0, __float_as_int(v)));
+    EMOE_DPP_REDUCE(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Phase 2 for one token, run by one wavefront.
@@ -290,6 +314,7 @@ __global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
     if (kbeg < kend) load_chunk(kbeg, xc, wc);
     for (int k0 = kbeg; k0 < kend; k0 += 128) {
         if (k0 + 128 < kend) load_chunk(k0 + 128, xn, wn);
+        __builtin_amdgcn_sched_barrier(0);  // the prefetch must be issued before this chunk's MFMAs, not after
         if constexpr (sizeof(WT) == 2) {
 #pragma unroll
             for (int a = 0; a < ET; ++a)
@@ -387,6 +412,12 @@ hipError_t launch_gate_logits_t(const Pass &p, hipStream_t st)
     return hipGetLastError();
 }
 
+#ifndef EMOE_G21
+#define EMOE_G21 192
+#endif
+#ifndef EMOE_G42
+#define EMOE_G42 192
+#endif
 template <typename WT>
 hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
 {
@@ -394,8 +425,8 @@ hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
     auto blocks = [&](int tt, int et) { return ((p.T + 16 * tt - 1) / (16 * tt)) * ((p.E + 64 * et - 1) / (64 * et)); };
     hipError_t e;
     if (p.T <= 256)                                   e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
-    else if (sizeof(WT) == 2 && blocks(4, 2) >= 192)  e = launch_gate_logits_t<WT, 4, 2, false>(p, st);
-    else if (blocks(2, 1) >= 192)                     e = launch_gate_logits_t<WT, 2, 1, false>(p, st);
+    else if (sizeof(WT) == 2 && blocks(4, 2) >= EMOE_G42)  e = launch_gate_logits_t<WT, 4, 2, false>(p, st);
+    else if (blocks(2, 1) >= EMOE_G21)                e = launch_gate_logits_t<WT, 2, 1, false>(p, st);
     else                                              e = launch_gate_logits_t<WT, 1, 1, false>(p, st);
     if (e != hipSuccess) return e;
     const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);

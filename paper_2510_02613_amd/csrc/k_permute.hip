@@ -7,9 +7,10 @@
 // the kernels here translate logical expert ids to physical weight slots on every
 // pass and never assume a placement.
 //
-//   k_slot_hist  per block of 256 assignments: slot lookup, LDS histogram, and the
+//   k_slot_hist  per block of 1024 assignments: slot lookup, LDS histogram, and the
 //                rank of every assignment among the block's earlier assignments to
-//                the same slot (deterministic: token order).
+//                the same slot (deterministic: token order): lane scan inside a
+//                wavefront, wavefronts take turns on the LDS counts.
 //   k_slot_scan  one block: per-slot running sum over the blocks, exclusive prefix
 //                sum over slots (LDS scan), and the M-tile list for the GEMMs.
 //   k_slot_place row = offsets[slot] + block base + rank; perm[row] = token,
@@ -22,16 +23,15 @@
 namespace emoe {
 namespace {
 
-constexpr int kThreads = kAssignPerBlock;
+constexpr int kThreads = 256;               // scan and place kernels
+constexpr int kHistThreads = kAssignPerBlock;  // one thread per assignment, 16 wavefronts
 
-__global__ __launch_bounds__(kThreads) void k_slot_hist(Pass p)
+__global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
 {
-    extern __shared__ int32_t sm[];
-    int32_t *hist = sm;          // [S]
-    int32_t *slots = sm + p.S;   // [kThreads]
-    const int tid = threadIdx.x;
-    for (int s = tid; s < p.S; s += kThreads) hist[s] = 0;
-    const int a = blockIdx.x * kThreads + tid;
+    extern __shared__ int32_t hist[];   // [S] rows per slot seen so far in this block
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int s = tid; s < p.S; s += kHistThreads) hist[s] = 0;
+    const int a = blockIdx.x * kHistThreads + tid;
     const int n_assign = p.T * p.kk;
     int slot = -1;
     if (a < n_assign) {
@@ -42,15 +42,24 @@ __global__ __launch_bounds__(kThreads) void k_slot_hist(Pass p)
             slot = p.map[p.E + (j - p.k)];
         }
     }
-    slots[tid] = slot;
-    __syncthreads();
-    if (slot >= 0) atomicAdd(&hist[slot], 1);
+    // rank among the earlier lanes of this wavefront with the same slot
     int rank = 0;
-    if (slot >= 0)
-        for (int i = 0; i < tid; ++i) rank += (slots[i] == slot);
-    if (a < n_assign) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
+    for (int i = 0; i < 63; ++i) {
+        const int si = __builtin_amdgcn_readlane(slot, i);
+        rank += (lane > i && si == slot && slot >= 0) ? 1 : 0;
+    }
     __syncthreads();
-    for (int s = tid; s < p.S; s += kThreads) p.blk_hist[(size_t)blockIdx.x * p.S + s] = hist[s];
+    // wavefronts take turns in order: read the slot's running count, then add this wavefront's rows
+    for (int w = 0; w < kHistThreads / 64; ++w) {
+        if (wave == w && slot >= 0) {
+            rank += hist[slot];
+        }
+        __syncthreads();
+        if (wave == w && slot >= 0) atomicAdd(&hist[slot], 1);
+        __syncthreads();
+    }
+    if (a < n_assign) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
+    for (int s = tid; s < p.S; s += kHistThreads) p.blk_hist[(size_t)blockIdx.x * p.S + s] = hist[s];
 }
 
 // exclusive scan of v over the 256 threads of the block (v is per-thread), returns the
@@ -140,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
     int row = -1;
     if (sr >= 0) {
         const int slot = sr >> 12, rank = sr & 0xfff;
-        row = p.offs[slot] + p.blk_hist[(size_t)blockIdx.x * p.S + slot] + rank;
+        row = p.offs[slot] + p.blk_hist[(size_t)(a / kAssignPerBlock) * p.S + slot] + rank;
         p.perm[row] = a / p.kk;
     }
     p.inv[a] = row;
@@ -151,10 +160,11 @@ __global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
 hipError_t launch_permute(const Pass &p, int tile_rows, hipStream_t st)
 {
     const int n_assign = p.T * p.kk;
-    const int nb = (n_assign + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kThreads), sizeof(int32_t) * (p.S + kThreads), st, p);
+    const int nb = (n_assign + kAssignPerBlock - 1) / kAssignPerBlock;   // histogram blocks
+    const int nbp = (n_assign + kThreads - 1) / kThreads;                 // placement blocks
+    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * p.S, st, p);
     hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows);
-    hipLaunchKernelGGL(k_slot_place, dim3(nb), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL(k_slot_place, dim3(nbp), dim3(kThreads), 0, st, p);
     return hipGetLastError();
 }
 

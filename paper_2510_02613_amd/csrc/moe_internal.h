@@ -51,7 +51,7 @@ struct Pass {
     int32_t max_tiles;
 };
 
-constexpr int kAssignPerBlock = 256;  // assignments ranked by one block of the permute kernels
+constexpr int kAssignPerBlock = 1024;  // assignments ranked by one block of the slot histogram kernel
 
 hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st);
 hipError_t launch_gate(const Pass &p, hipStream_t st);
