@@ -388,6 +388,163 @@ __global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
         }
 }
 
+// LDS-tiled logits kernel for prefill-sized batches.  A workgroup owns 16*TBT tokens x 64*EBT
+// experts; the token tile and the router tile of a K-step of 64 are staged once in LDS (global ->
+// registers -> LDS, next step's loads in flight during this step's MFMAs) and shared by the four
+// wavefronts, wavefront w taking expert tiles w*EBT .. of 16 experts each.  Tile rows are 128
+// bytes with their 16-byte chunks XOR-swizzled so that the 16 rows a half-wavefront reads for one
+// operand fall into 16 distinct bank groups.
+// fp32 router weights are split on the fly into three bf16 planes hi + mid + lo (each the
+// truncated top 8 mantissa bits of what is left: the split is exact), so that x . w is three bf16
+// MFMAs whose products are all exact and whose sum is accumulated in fp32: the same products and
+// the same accumulator width as an fp32 multiply-add chain.
+__device__ __forceinline__ int gate_swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
+
+template <typename WT, int TBT, int EBT>
+__global__ __launch_bounds__(kThreads) void k_gate_logits_lds(Pass p)
+{
+    constexpr int P = sizeof(WT) == 2 ? 1 : 3;          // bf16 planes per router tile
+    constexpr int TB = 16 * TBT, EB = 64 * EBT;
+    constexpr int XCH = TB * 8, WCH = EB * 8;           // 16-byte chunks per tile (per plane)
+    constexpr int XL = (XCH + kThreads - 1) / kThreads; // staging loads per thread
+    constexpr int WL = WCH / kThreads * (P == 3 ? 2 : 1);   // fp32: 8 floats = 2 loads per 8-element chunk
+    constexpr int WCL = WCH / kThreads;                 // 8-element chunks per thread
+    __shared__ uint4 lds[2][XCH + P * WCH];
+    const int E = p.E, H = p.H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * TB, e0 = blockIdx.y * EB;
+    const uint16_t *x = (const uint16_t *)p.x;
+    const WT *wr = (const WT *)p.router_w;
+
+    uint4 xa[XL], wa[WL], xb[XL], wb[WL];   // two register stages: K-steps kt+1 and kt+2 are in flight
+    auto load_global = [&](int k0, uint4 *xreg, uint4 *wreg) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int c = tid + i * kThreads, row = c >> 3, ch = c & 7;
+            const int k = k0 + ch * 8;
+            xreg[i] = (c < XCH && k < H) ? *(const uint4 *)(x + (size_t)min(t0 + row, p.T - 1) * H + k) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WCL; ++i) {
+            const int c = tid + i * kThreads, row = c >> 3, ch = c & 7;
+            const int k = k0 + ch * 8;
+            const WT *src = wr + (size_t)min(e0 + row, E - 1) * H + k;
+            if constexpr (P == 1) {
+                wreg[i] = (k < H) ? *(const uint4 *)src : make_uint4(0, 0, 0, 0);
+            } else {
+                wreg[2 * i] = (k < H) ? *(const uint4 *)src : make_uint4(0, 0, 0, 0);
+                wreg[2 * i + 1] = (k < H) ? *(const uint4 *)(src + 4) : make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto store_lds = [&](int buf, const uint4 *xreg, const uint4 *wreg) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int c = tid + i * kThreads, row = c >> 3, ch = c & 7;
+            if (c < XCH) lds[buf][row * 8 + (ch ^ gate_swz(row))] = xreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < WCL; ++i) {
+            const int c = tid + i * kThreads, row = c >> 3, ch = c & 7;
+            const int at = XCH + row * 8 + (ch ^ gate_swz(row));
+            if constexpr (P == 1) {
+                lds[buf][at] = wreg[i];
+            } else {
+                const uint32_t *f = (const uint32_t *)&wreg[2 * i];   // 8 fp32 bit patterns
+                uint32_t hi[8], mid[8], lo[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    hi[e] = f[e] & 0xffff0000u;
+                    const float r1 = __uint_as_float(f[e]) - __uint_as_float(hi[e]);
+                    mid[e] = __float_as_uint(r1) & 0xffff0000u;
+                    const float r2 = r1 - __uint_as_float(mid[e]);
+                    lo[e] = __float_as_uint(r2);   // at most 8 significant bits left: already a bf16 value
+                }
+                auto pack = [](const uint32_t *v) {
+                    return make_uint4((v[0] >> 16) | v[1], (v[2] >> 16) | v[3], (v[4] >> 16) | v[5], (v[6] >> 16) | v[7]);
+                };
+                uint32_t lom[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) lom[e] = lo[e] & 0xffff0000u;
+                lds[buf][at] = pack(hi);
+                lds[buf][at + WCH] = pack(mid);
+                lds[buf][at + 2 * WCH] = pack(lom);
+            }
+        }
+    };
+
+    f32x4 acc[EBT][TBT];
+#pragma unroll
+    for (int a = 0; a < EBT; ++a)
+#pragma unroll
+        for (int tb = 0; tb < TBT; ++tb) acc[a][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int n = lane & 15, q = lane >> 4;
+
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int ch = ks * 4 + q;
+            bf16x8 xf[TBT];
+#pragma unroll
+            for (int tb = 0; tb < TBT; ++tb) {
+                const int row = tb * 16 + n;
+                const uint4 v = lds[buf][row * 8 + (ch ^ gate_swz(row))];
+                xf[tb] = *(const bf16x8 *)&v;
+            }
+#pragma unroll
+            for (int a = 0; a < EBT; ++a) {
+                const int row = (wave * EBT + a) * 16 + n;
+#pragma unroll
+                for (int pl = 0; pl < P; ++pl) {
+                    const uint4 v = lds[buf][XCH + pl * WCH + row * 8 + (ch ^ gate_swz(row))];
+                    const bf16x8 wf = *(const bf16x8 *)&v;
+#pragma unroll
+                    for (int tb = 0; tb < TBT; ++tb)
+                        acc[a][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf[tb], acc[a][tb], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // Loads past the end of K are predicated off (they return zeros), so the pipeline needs no tail code.
+    const int KT = (H + 63) / 64;
+    load_global(0, xa, wa);
+    load_global(64, xb, wb);
+    store_lds(0, xa, wa);
+    load_global(128, xa, wa);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        multiply(0);                          // K-step kt
+        store_lds(1, xb, wb);                 // K-step kt+1 (loaded one whole iteration ago)
+        load_global((kt + 3) * 64, xb, wb);
+        __syncthreads();
+        if (kt + 1 < KT) multiply(1);         // K-step kt+1
+        store_lds(0, xa, wa);                 // K-step kt+2
+        load_global((kt + 4) * 64, xa, wa);
+        __syncthreads();
+    }
+    // lane holds token n of each token tile, experts 4q + r of each of its expert tiles
+#pragma unroll
+    for (int a = 0; a < EBT; ++a)
+#pragma unroll
+        for (int tb = 0; tb < TBT; ++tb) {
+            const int t = t0 + tb * 16 + n;
+            const int e = e0 + (wave * EBT + a) * 16 + 4 * q;
+            if (t < p.T) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (e + r < E) p.logits[(size_t)t * E + e + r] = acc[a][tb][r] + (p.logit_bias ? p.logit_bias[e + r] : 0.f);
+            }
+        }
+}
+
+template <typename WT, int TBT, int EBT>
+hipError_t launch_gate_logits_lds(const Pass &p, hipStream_t st)
+{
+    dim3 grid((p.T + 16 * TBT - 1) / (16 * TBT), (p.E + 64 * EBT - 1) / (64 * EBT));
+    hipLaunchKernelGGL((k_gate_logits_lds<WT, TBT, EBT>), grid, dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
 {
     extern __shared__ float smem[];
@@ -422,12 +579,10 @@ template <typename WT>
 hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
 {
     // pick the split that gives the chip enough workgroups
-    auto blocks = [&](int tt, int et) { return ((p.T + 16 * tt - 1) / (16 * tt)) * ((p.E + 64 * et - 1) / (64 * et)); };
     hipError_t e;
-    if (p.T <= 256)                                   e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
-    else if (sizeof(WT) == 2 && blocks(4, 2) >= EMOE_G42)  e = launch_gate_logits_t<WT, 4, 2, false>(p, st);
-    else if (blocks(2, 1) >= EMOE_G21)                e = launch_gate_logits_t<WT, 2, 1, false>(p, st);
-    else                                              e = launch_gate_logits_t<WT, 1, 1, false>(p, st);
+    if (p.T <= 256)                     e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
+    else if (p.E > 64 && p.T >= 8192)   e = launch_gate_logits_lds<WT, 4, 2>(p, st);   // 64 tokens x 128 experts
+    else                                e = launch_gate_logits_lds<WT, 2, 1>(p, st);   // 32 tokens x 64 experts
     if (e != hipSuccess) return e;
     const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);
     hipLaunchKernelGGL(k_gate_select, dim3((p.T + 3) / 4), dim3(kThreads), smem, st, p);
