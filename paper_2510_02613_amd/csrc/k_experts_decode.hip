@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
         if (col < N) {
             float h[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) h[r] = acc_a[r] / (1.f + __expf(-acc_a[r])) * acc_b[r];
+            for (int r = 0; r < 4; ++r) h[r] = silu_mul(acc_a[r], acc_b[r]);
             *(uint2 *)(O + col) = pack(h[0], h[1], h[2], h[3]);
         }
     } else {

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_expert_gemm_mfma(Pass p)
                     float g = acc[a][c][q * 4 + e];
                     if (kFirst) {
                         const float u = acc[a + TN / 2][c][q * 4 + e];
-                        g = g / (1.f + __expf(-g)) * u;
+                        g = silu_mul(g, u);
                     }
                     v[e] = f32_to_bf16(g);
                 }

@@ -124,12 +124,15 @@ __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr,
     }
 }
 
-// Orders this wavefront's own LDS traffic (writes before, reads after).
+// Orders this wavefront's own LDS traffic (writes before, reads after) WITHOUT waiting for its
+// global stores: LDS instructions of one wavefront execute in order, so all that is needed is
+// that the compiler keeps the order and that outstanding LDS operations have retired.  (A
+// release/acquire fence here would also drain the vector-memory counter, i.e. stall every token
+// tile of the epilogue on the round trip of the previous tile's stores.)
 __device__ __forceinline__ void wave_lds_sync()
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Wait until at most n of this wavefront's loads are still in flight (they complete in order).
@@ -258,7 +261,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
                     float g = acc[a][t][q * 4 + e];
                     if (kFirst) {
                         const float u = acc[a][t][(q + 2) * 4 + e];
-                        g = g / (1.f + __expf(-g)) * u;
+                        g = silu_mul(g, u);
                     }
                     v[e] = f32_to_bf16(g);
                 }

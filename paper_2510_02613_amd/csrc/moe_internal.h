@@ -75,12 +75,17 @@ constexpr int kGenericTileRows = 32;  // M-tile of the plain expert kernels
 // ---- small device helpers ---------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// fp32 -> bf16, round to nearest even (one v_cvt_pk_bf16_f32 per pair on gfx950)
 __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest, ties to even
-    return (uint16_t)(u >> 16);
+    const __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, b);
+}
+
+// silu(g) * u with the hardware exp2 / reciprocal (about 1 ulp each): g * u / (1 + exp(-g))
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u;
 }
 
 template <typename T> __device__ __forceinline__ float load_f32(const T *p, size_t i);
