@@ -8,9 +8,12 @@
 //  * Every expert's weights are used by only ~256 rows, so the layer streams all
 //    resident weights from HBM once per pass: the kernel must keep HBM busy.  A
 //    compute unit has to hold ~48 KB of weight bytes in flight to cover HBM latency
-//    at full bandwidth; the K loop therefore runs a 6-deep ring of 16 KB weight
-//    steps (K-step 32, five in flight) beside a 3-deep ring of token steps (those
-//    come from L2) and only ever waits for the OLDEST step of each.
+//    at full bandwidth, and HBM delivers whole 128-byte lines much faster than half
+//    lines.  The weight rows therefore travel in steps of 64 k (one full line per
+//    row, 32 KB per step) through their own 3-deep ring, two steps in flight, beside
+//    a 3-deep ring of token steps of 32 k (those come from L2); each ring has its own
+//    loader wavefronts, because a wavefront's loads complete in order and the two
+//    streams run at different distances.  Only the OLDEST step of a ring is waited for.
 //  * A compute unit pulls ~64 B/clk from L2 but retires 4096 bf16 flops/clk, so a
 //    tile must reuse staged bytes >= 64 times: up to 320 token rows x 256 weight
 //    rows gives 114-142 (a 128 x 128 tile gives exactly 64 and is bandwidth bound).
@@ -26,10 +29,10 @@
 // wavefronts per SIMD so that one's LDS waits hide under the other's MFMAs.
 //
 // Staging: global_load_lds_dwordx4 -- global memory straight into LDS, 16 bytes per
-// lane, no VGPR round trip, no ds_write.  One instruction fills 16 rows x 64 bytes;
-// lane i supplies row i/4 and lands in 16-byte slot i%4, so it FETCHES chunk
-// (i%4) ^ swz(row): the XOR swizzle that keeps the 16-byte operand reads conflict
-// free is applied on the global side.
+// lane, no VGPR round trip, no ds_write.  One instruction fills 1 KB: 16 token rows
+// x 64 bytes or 8 weight rows x 128 bytes; lane i lands in 16-byte slot i of the
+// piece, so it FETCHES the chunk that belongs there: the XOR swizzle that keeps the
+// 16-byte operand reads conflict free is applied on the global side.
 //
 // GEMM-1 packs every 32-row MFMA weight tile as 16 gate rows followed by the 16
 // matching up rows; in the 32x32 accumulator layout a lane then holds gate value r
@@ -55,7 +58,7 @@ constexpr int kBM = kMaxTT * 32;           // 320: a whole group with its ragged
 constexpr int kRows = kBN + kBM;           // LDS rows per stage
 constexpr int kBKW = 64;                   // weight K-step: 128 bytes per row = one whole cache line
 constexpr int kWStage = kBN * kBKW * 2;    // 32 KB of weight rows per weight step
-constexpr int kXStage = kBM * kBK * 2;     // 16 KB of token rows per K-step
+constexpr int kXStage = kBM * kBK * 2;     // 20 KB of token rows per K-step
 constexpr int kNW = 3;                     // weight ring depth: 2 weight steps (64 KB) in flight from HBM
 constexpr int kNX = 3;                     // token ring depth: token rows come from L2
 constexpr int kWPieces = kWStage / 1024 / 4;   // 8: 1 KB pieces (8 rows x 128 B) per weight-loader wavefront per weight step
@@ -106,10 +109,10 @@ __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, u
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
-// Loader roles: wavefronts 0-3 stream the weight rows, wavefronts 4-7 the token rows, 4 pieces
-// each per K-step.  The split matters because a wavefront's loads complete in order: a single
-// wavefront issuing both could not keep five weight steps in flight while waiting for the much
-// younger token step.
+// Loader roles: wavefronts 0-3 stream the weight rows (8 pieces each per weight step),
+// wavefronts 4-7 the token rows (up to 5 pieces each per K-step).  The split matters because a
+// wavefront's loads complete in order: a single wavefront issuing both could not keep two weight
+// steps in flight while waiting for the much younger token step.
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
     if (c.wave < 4) {

@@ -569,12 +569,6 @@ hipError_t launch_gate_logits_t(const Pass &p, hipStream_t st)
     return hipGetLastError();
 }
 
-#ifndef EMOE_G21
-#define EMOE_G21 192
-#endif
-#ifndef EMOE_G42
-#define EMOE_G42 192
-#endif
 template <typename WT>
 hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
 {
