@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel events inside the timed region (roofline then is null)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the two measuring-stick kernels (sustained MFMA rate, streaming read) after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (counter calibration for rocprofv3 --pmc) and exit")
     return ap.parse_args()
@@ -195,9 +197,40 @@ def main():
         "roofline": roofline,
     }
 
+    if not args.no_ceilings:
+        result["ceilings"] = measure_ceilings(torch, B, layer, stream)
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, args.cpu_seconds)
     print(json.dumps(result))
+
+
+def measure_ceilings(torch, B, layer, stream):
+    """What this chip sustains with nothing else in the way (after the timed region, same process):
+    a register-only bf16 MFMA stream shaped like the expert kernels' wavefronts, and one plain
+    streaming read of the layer's own W13 pool.  Context for the roofline fractions, which are
+    taken against the data-sheet peaks."""
+    sink = torch.zeros(1, dtype=torch.float32, device=layer.w13.device)
+    s = stream.cuda_stream
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    w_ptr, w_bytes = layer.w13.data_ptr(), layer.w13.numel() * layer.w13.element_size()
+    B.moe_ceiling_mfma(512, 2000, sink.data_ptr(), s)          # warm both
+    B.moe_ceiling_stream(w_ptr, w_bytes, sink.data_ptr(), s)
+    ev[0].record(stream)
+    flops = B.moe_ceiling_mfma(2048, 20000, sink.data_ptr(), s)   # about 10 ms
+    ev[1].record(stream)
+    ev[2].record(stream)
+    reps = max(1, int(8e9 // w_bytes))
+    for _ in range(reps):
+        B.moe_ceiling_stream(w_ptr, w_bytes, sink.data_ptr(), s)
+    ev[3].record(stream)
+    torch.cuda.synchronize()
+    t_m = ev[0].elapsed_time(ev[1]) * 1e-3
+    t_s = ev[2].elapsed_time(ev[3]) * 1e-3
+    return {"mfma_bf16_tflops": flops / t_m / 1e12, "mfma_ms": t_m * 1e3,
+            "stream_read_gbs": reps * w_bytes / t_s / 1e9, "stream_bytes": w_bytes, "stream_reps": reps,
+            "note": "sustained rates of this chip: register-only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup), "
+                    "and a plain read of the W13 pool"}
 
 
 def cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, target_s):

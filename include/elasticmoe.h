@@ -185,6 +185,21 @@ enum { MOE_PHASE_GATE = 0, MOE_PHASE_PERMUTE = 1, MOE_PHASE_GEMM1 = 2, MOE_PHASE
 moe_status_t moe_profile_enable(moe_layer_t *layer, int32_t enable);
 moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
 
+/*
+ * Measuring sticks for benchmarks (not part of the method): what this chip sustains
+ * with nothing else in the way, so that a fraction of the data-sheet peak can be read
+ * beside the fraction of what is reachable.  Both only enqueue one kernel on
+ * `hip_stream`; the caller times it.  `sink` is a device float the kernels may
+ * write (they practically never do); nothing is allocated.
+ *   moe_ceiling_mfma:   `blocks` workgroups of 8 wavefronts each run `iters` rounds of
+ *                       8 independent register-only v_mfma_f32_32x32x16_bf16;
+ *                       *flops receives the flops of the launch.
+ *   moe_ceiling_stream: reads `bytes` (rounded down to 16) of device memory at `buf`
+ *                       (16-byte aligned) once, 16 bytes per lane.
+ */
+moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, float *sink, void *hip_stream, double *flops);
+moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void *hip_stream);
+
 /* Frees the host object only (the library owns no device memory). NULL is allowed. */
 void moe_layer_destroy(moe_layer_t *layer);
 

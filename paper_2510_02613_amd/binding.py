@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_M
 # every symbol include/elasticmoe.h declares
 EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
-           "moe_profile_read")
+           "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream")
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
 
@@ -84,6 +84,11 @@ def lib() -> ctypes.CDLL:
         L.moe_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.moe_profile_read.restype = ctypes.c_int
         L.moe_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)]
+        L.moe_ceiling_mfma.restype = ctypes.c_int
+        L.moe_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.POINTER(ctypes.c_double)]
+        L.moe_ceiling_stream.restype = ctypes.c_int
+        L.moe_ceiling_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_last_error.argtypes = []
         _lib = L
@@ -148,6 +153,18 @@ def moe_profile_read(layer, back: int = 0):
     ms = (ctypes.c_float * MOE_N_PHASES)()
     _check(lib().moe_profile_read(layer, back, ms))
     return [float(v) for v in ms]
+
+
+def moe_ceiling_mfma(blocks: int, iters: int, sink_ptr: int, stream: int = 0) -> float:
+    """Enqueue the register-only MFMA stream; returns the flops of the launch."""
+    flops = ctypes.c_double()
+    _check(lib().moe_ceiling_mfma(blocks, iters, ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream), ctypes.byref(flops)))
+    return flops.value
+
+
+def moe_ceiling_stream(buf_ptr: int, nbytes: int, sink_ptr: int, stream: int = 0) -> None:
+    """Enqueue one streaming read of nbytes of device memory."""
+    _check(lib().moe_ceiling_stream(ctypes.c_void_p(buf_ptr), ctypes.c_size_t(nbytes), ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream)))
 
 
 def moe_layer_destroy(layer) -> None:
