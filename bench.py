@@ -212,25 +212,29 @@ def measure_ceilings(torch, B, layer, stream):
     taken against the data-sheet peaks."""
     sink = torch.zeros(1, dtype=torch.float32, device=layer.w13.device)
     s = stream.cuda_stream
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     w_ptr, w_bytes = layer.w13.data_ptr(), layer.w13.numel() * layer.w13.element_size()
-    B.moe_ceiling_mfma(512, 2000, sink.data_ptr(), s)          # warm both
+    B.moe_ceiling_mfma(512, 2000, False, sink.data_ptr(), s)          # warm all three
+    B.moe_ceiling_mfma(512, 2000, True, sink.data_ptr(), s)
     B.moe_ceiling_stream(w_ptr, w_bytes, sink.data_ptr(), s)
     ev[0].record(stream)
-    flops = B.moe_ceiling_mfma(2048, 20000, sink.data_ptr(), s)   # about 10 ms
+    flops = B.moe_ceiling_mfma(2048, 20000, False, sink.data_ptr(), s)   # tens of ms each
     ev[1].record(stream)
+    B.moe_ceiling_mfma(2048, 20000, True, sink.data_ptr(), s)
     ev[2].record(stream)
     reps = max(1, int(8e9 // w_bytes))
     for _ in range(reps):
         B.moe_ceiling_stream(w_ptr, w_bytes, sink.data_ptr(), s)
     ev[3].record(stream)
     torch.cuda.synchronize()
-    t_m = ev[0].elapsed_time(ev[1]) * 1e-3
+    t_c = ev[0].elapsed_time(ev[1]) * 1e-3
+    t_r = ev[1].elapsed_time(ev[2]) * 1e-3
     t_s = ev[2].elapsed_time(ev[3]) * 1e-3
-    return {"mfma_bf16_tflops": flops / t_m / 1e12, "mfma_ms": t_m * 1e3,
+    return {"mfma_bf16_tflops_constant_operands": flops / t_c / 1e12,
+            "mfma_bf16_tflops_random_operands": flops / t_r / 1e12,
             "stream_read_gbs": reps * w_bytes / t_s / 1e9, "stream_bytes": w_bytes, "stream_reps": reps,
-            "note": "sustained rates of this chip: register-only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup), "
-                    "and a plain read of the W13 pool"}
+            "note": "sustained rates of this chip: register-only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup) "
+                    "on constant and on changing pseudo-random operands, and a plain read of the W13 pool"}
 
 
 def cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, target_s):

@@ -193,11 +193,15 @@ moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
  * write (they practically never do); nothing is allocated.
  *   moe_ceiling_mfma:   `blocks` workgroups of 8 wavefronts each run `iters` rounds of
  *                       8 independent register-only v_mfma_f32_32x32x16_bf16;
- *                       *flops receives the flops of the launch.
+ *                       *flops receives the flops of the launch.  random_operands != 0
+ *                       multiplies pseudo-random values in (-1, 1) that change from one
+ *                       MFMA to the next (the sustained rate under realistic switching
+ *                       power), 0 small constants (the issue-rate ceiling).
  *   moe_ceiling_stream: reads `bytes` (rounded down to 16) of device memory at `buf`
  *                       (16-byte aligned) once, 16 bytes per lane.
  */
-moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, float *sink, void *hip_stream, double *flops);
+moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, int32_t random_operands, float *sink,
+                              void *hip_stream, double *flops);
 moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void *hip_stream);
 
 /* Frees the host object only (the library owns no device memory). NULL is allowed. */

@@ -85,7 +85,7 @@ def lib() -> ctypes.CDLL:
         L.moe_profile_read.restype = ctypes.c_int
         L.moe_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)]
         L.moe_ceiling_mfma.restype = ctypes.c_int
-        L.moe_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+        L.moe_ceiling_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.POINTER(ctypes.c_double)]
         L.moe_ceiling_stream.restype = ctypes.c_int
         L.moe_ceiling_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
@@ -155,10 +155,11 @@ def moe_profile_read(layer, back: int = 0):
     return [float(v) for v in ms]
 
 
-def moe_ceiling_mfma(blocks: int, iters: int, sink_ptr: int, stream: int = 0) -> float:
+def moe_ceiling_mfma(blocks: int, iters: int, random_operands: bool, sink_ptr: int, stream: int = 0) -> float:
     """Enqueue the register-only MFMA stream; returns the flops of the launch."""
     flops = ctypes.c_double()
-    _check(lib().moe_ceiling_mfma(blocks, iters, ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream), ctypes.byref(flops)))
+    _check(lib().moe_ceiling_mfma(blocks, iters, int(bool(random_operands)), ctypes.c_void_p(sink_ptr),
+                                  ctypes.c_void_p(stream), ctypes.byref(flops)))
     return flops.value
 
 

@@ -14,11 +14,24 @@ constexpr int kThreads = 512;        // 8 wavefronts, two per SIMD, as in the la
 constexpr int kChains = 8;           // independent accumulators per wavefront
 
 // Register-only v_mfma_f32_32x32x16_bf16 stream: `iters` rounds of kChains independent MFMAs.
-__global__ __launch_bounds__(kThreads) void k_ceiling_mfma(int iters, float *sink)
+// `random_operands` != 0 feeds the multipliers pseudo-random values in (-1, 1) that change from
+// one MFMA to the next (the power such data draws is what sets the sustained clock of real
+// kernels); 0 feeds small constants (the issue-rate ceiling).
+__global__ __launch_bounds__(kThreads) void k_ceiling_mfma(int iters, int random_operands, float *sink)
 {
-    bf16x8 a, b;
+    bf16x8 a[4], b[4];
+    uint32_t h = (threadIdx.x + 1u) * 0x9e3779b9u + blockIdx.x * 0x85ebca6bu;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(float)((threadIdx.x + i) & 3); b[i] = (__bf16)(float)((threadIdx.x >> 2) & 1); }
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            h = h * 1664525u + 1013904223u;
+            const float ra = random_operands ? (float)(int)(h >> 8 & 0xffff) * (1.f / 32768.f) - 1.f : (float)((threadIdx.x + i) & 3);
+            h = h * 1664525u + 1013904223u;
+            const float rb = random_operands ? (float)(int)(h >> 8 & 0xffff) * (1.f / 32768.f) - 1.f : (float)((threadIdx.x >> 2) & 1);
+            a[j][i] = (__bf16)ra;
+            b[j][i] = (__bf16)rb;
+        }
     f32x16 acc[kChains];
 #pragma unroll
     for (int c = 0; c < kChains; ++c)
@@ -26,14 +39,14 @@ __global__ __launch_bounds__(kThreads) void k_ceiling_mfma(int iters, float *sin
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+        for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c & 3], b[(c + (c >> 2)) & 3], acc[c], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
     for (int c = 0; c < kChains; ++c)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s += acc[c][r];
-    if (s == 123456.789f) sink[0] = s;   // keeps the chain alive; practically never true
+    if (s == 123456.789f) sink[0] = s;   // keeps the chains alive; practically never true
 }
 
 // Plain streaming read: 16 bytes per lane, consecutive lanes on consecutive addresses, grid-stride.
@@ -52,9 +65,9 @@ __global__ __launch_bounds__(256) void k_ceiling_stream(const uint4 *__restrict_
 
 double ceiling_mfma_flops(int blocks, int iters) { return (double)blocks * (kThreads / 64) * (double)iters * kChains * 2.0 * 32 * 32 * 16; }
 
-hipError_t launch_ceiling_mfma(int blocks, int iters, float *sink, hipStream_t st)
+hipError_t launch_ceiling_mfma(int blocks, int iters, int random_operands, float *sink, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_ceiling_mfma, dim3(blocks), dim3(kThreads), 0, st, iters, sink);
+    hipLaunchKernelGGL(k_ceiling_mfma, dim3(blocks), dim3(kThreads), 0, st, iters, random_operands, sink);
     return hipGetLastError();
 }
 

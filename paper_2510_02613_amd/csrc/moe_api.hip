@@ -152,12 +152,12 @@ moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf,
     return MOE_OK;
 }
 
-moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, float *sink, void *hip_stream, double *flops)
+moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, int32_t random_operands, float *sink, void *hip_stream, double *flops)
 {
     if (blocks <= 0 || iters <= 0 || !sink || !flops) return fail(MOE_ERR_ARG, "blocks and iters must be positive, sink and flops non-NULL");
     if (blocks > (1 << 20) || iters > (1 << 24)) return fail(MOE_ERR_ARG, "blocks <= 2^20 and iters <= 2^24");
     *flops = ceiling_mfma_flops(blocks, iters);
-    const hipError_t e = launch_ceiling_mfma(blocks, iters, sink, (hipStream_t)hip_stream);
+    const hipError_t e = launch_ceiling_mfma(blocks, iters, random_operands, sink, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail(MOE_ERR_HIP, "ceiling launch failed: %s", hipGetErrorString(e));
     return MOE_OK;
 }

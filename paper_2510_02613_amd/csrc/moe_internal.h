@@ -64,7 +64,7 @@ int mfma_tile_rows();
 hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st);
 int mfma8_tile_rows();
 bool mfma8_supports(const Pass &p);
-hipError_t launch_ceiling_mfma(int blocks, int iters, float *sink, hipStream_t st);
+hipError_t launch_ceiling_mfma(int blocks, int iters, int random_operands, float *sink, hipStream_t st);
 double ceiling_mfma_flops(int blocks, int iters);
 hipError_t launch_ceiling_stream(const void *buf, size_t bytes, float *sink, hipStream_t st);
 // weight-streaming variant for decode-sized batches (M-tiles of 16 rows)
