@@ -52,6 +52,7 @@ def _load():
         _lib = ctypes.CDLL(build())
         _lib.oracle_route.restype = None
         _lib.oracle_forward.restype = None
+        _lib.oracle_forward_routed.restype = None
         _lib.oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -108,13 +109,13 @@ def _cfg(spec: LayerSpec, x, router_w, w13=None) -> _Cfg:
     if w13 is not None and _storage(w13) != act:
         raise TypeError("x and expert weights must use the same storage type")
     assert x.shape == (spec.T, spec.H), (x.shape, spec)
-    assert router_w.shape == (spec.E, spec.H)
+    assert router_w is None or router_w.shape == (spec.E, spec.H)
     assert spec.E % max(spec.n_group, 1) == 0 and spec.n_group <= 256
     assert 1 <= spec.k <= spec.E
     return _Cfg(spec.T, spec.H, spec.I, spec.E, spec.k, spec.S,
                 GATE_SOFTMAX if spec.gate == "softmax" else GATE_SIGMOID_GROUP,
                 spec.n_group, spec.topk_group, int(spec.renormalize), float(spec.routed_scale),
-                spec.n_shared, act, _storage(router_w))
+                spec.n_shared, act, act if router_w is None else _storage(router_w))
 
 
 def route(spec: LayerSpec, x, router_w, logit_bias=None, select_bias=None, want_scores=False):
@@ -159,4 +160,30 @@ def forward(spec: LayerSpec, x, router_w, w13, w2, expert_map, *, logit_bias=Non
                            ctypes.c_int32(int(shared_range[1])), _ptr(tok),
                            ctypes.c_int32(int(tok.size)), _ptr(forced),
                            ctypes.c_int32(int(identity_experts)), _ptr(out))
+    return out
+
+
+def forward_routed(spec: LayerSpec, x, w13, w2, expert_map, ids, wts, *, shared_slots: Sequence[int] = (),
+                   shared_range=(0, 0), tokens=None, identity_experts=False) -> np.ndarray:
+    """Layer output rows (fp64) when the routing is given: ids [T,k] int32 (ids outside [0,E)
+    are padding), wts [T,k] fp32 used as they are."""
+    x, w13, w2 = _c(x), _c(w13), _c(w2)
+    cfg = _cfg(spec, x, None, w13)
+    assert w13.shape == (spec.S, 2 * spec.I, spec.H), w13.shape
+    assert w2.shape == (spec.S, spec.H, spec.I), w2.shape
+    expert_map = _c(expert_map, np.int32)
+    assert expert_map.shape == (spec.E,)
+    assert expert_map.max(initial=-1) < spec.S and expert_map.min(initial=0) >= -1
+    shared = _c(np.asarray(list(shared_slots), dtype=np.int32))
+    assert shared.shape == (spec.n_shared,)
+    ids, wts = _c(ids, np.int32), _c(wts, np.float32)
+    assert ids.shape == (spec.T, spec.k) and wts.shape == (spec.T, spec.k)
+    tok = np.arange(spec.T, dtype=np.int32) if tokens is None else _c(tokens, np.int32)
+    assert tok.size == 0 or (tok.min() >= 0 and tok.max() < spec.T)
+    out = np.empty((tok.size, spec.H), dtype=np.float64)
+    _load().oracle_forward_routed(ctypes.byref(cfg), _ptr(x), _ptr(w13), _ptr(w2), _ptr(expert_map),
+                                  _ptr(shared), ctypes.c_int32(int(shared_range[0])),
+                                  ctypes.c_int32(int(shared_range[1])), _ptr(tok),
+                                  ctypes.c_int32(int(tok.size)), _ptr(ids), _ptr(wts),
+                                  ctypes.c_int32(int(identity_experts)), _ptr(out))
     return out

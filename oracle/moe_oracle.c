@@ -279,6 +279,44 @@ void oracle_forward(const oracle_cfg *cfg, const void *x, const void *router_w,
     }
 }
 
+/*
+ * Steps 5-7 alone, for a rank that receives tokens already routed (the input of an
+ * expert-parallel rank after the dispatch exchange, paper Sec. 2.1): the k expert
+ * ids and combine weights of every token are given instead of computed.
+ *   ids [T,k] int32 : logical expert ids; an id outside [0,E) is an assignment that
+ *                     does not exist (padding) and contributes nothing
+ *   wts [T,k] fp32  : combine weights, used as given (no renormalisation, no scale)
+ * Everything else as in oracle_forward.
+ */
+void oracle_forward_routed(const oracle_cfg *cfg, const void *x, const void *w13, const void *w2,
+                           const int32_t *expert_map, const int32_t *shared_slots,
+                           int32_t shared_begin, int32_t shared_end,
+                           const int32_t *tok, int32_t n_tok, const int32_t *ids, const float *wts,
+                           int32_t identity_experts, double *out)
+{
+#pragma omp parallel
+    {
+        double *a = malloc(sizeof(double) * cfg->I);
+#pragma omp for schedule(dynamic, 1)
+        for (int n = 0; n < n_tok; ++n) {
+            const int t = tok[n];
+            double *acc = out + (size_t)n * cfg->H;
+            for (int h = 0; h < cfg->H; ++h) acc[h] = 0.0;
+            for (int j = 0; j < cfg->k; ++j) {
+                const int e = ids[(size_t)t * cfg->k + j];
+                if (e < 0 || e >= cfg->E) continue;
+                const int slot = expert_map[e];               /* 5. locality */
+                if (slot < 0) continue;
+                expert_token(cfg, x, w13, w2, t, slot, (double)wts[(size_t)t * cfg->k + j], identity_experts, acc, a);
+            }
+            for (int i = 0; i < cfg->n_shared; ++i)           /* 7. shared experts */
+                if (t >= shared_begin && t < shared_end)
+                    expert_token(cfg, x, w13, w2, t, shared_slots[i], 1.0, identity_experts, acc, a);
+        }
+        free(a);
+    }
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP

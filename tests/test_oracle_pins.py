@@ -391,3 +391,53 @@ def test_bf16_rounding_helper_matches_torch():
     np.testing.assert_array_equal(ours, theirs)
     back = torch.from_numpy(theirs.view(np.int16)).view(torch.bfloat16).float().numpy()
     np.testing.assert_array_equal(bf16_bits_to_f32(ours), back)
+
+
+# ------------------------------------------------- routing given (steps 5-7) ----
+
+def test_routed_entry_against_library_ffn_with_arbitrary_ids_and_weights():
+    """Given ids and weights, a row is sum_j w_j * FFN_{map[id_j]}(x_t) from library ops;
+    remote experts (-1 in the map) and padding ids (outside [0,E)) add nothing; a repeated id counts twice."""
+    spec, x, wr, w13, w2 = small_layer(41, T=9, E=6, k=3, S=8)
+    g = rnd(42)
+    emap = np.array([5, -1, 0, 7, 2, -1], dtype=np.int32)          # experts 1 and 5 remote, slots scattered
+    ids = g.integers(0, spec.E, size=(spec.T, spec.k)).astype(np.int32)
+    ids[0] = [3, 3, 1]          # repeated id, remote id
+    ids[1] = [-1, 6, 2]         # two padding ids
+    wts = g.uniform(-1.0, 2.0, size=(spec.T, spec.k)).astype(np.float32)   # not normalised, may be negative
+    got = oracle.forward_routed(spec, x, w13, w2, emap, ids, wts)
+    want = np.zeros((spec.T, spec.H))
+    for t in range(spec.T):
+        for j in range(spec.k):
+            e = ids[t, j]
+            if 0 <= e < spec.E and emap[e] >= 0:
+                want[t] += float(wts[t, j]) * lib_ffn(x[t:t + 1], w13[emap[e]], w2[emap[e]])[0]
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_routed_entry_identity_experts_and_shared_range():
+    """Identity experts: row = (sum of the weights of local, existing ids + 1 per shared expert in range) * x."""
+    spec, x, wr, w13, w2 = small_layer(43, T=7, E=4, k=2, S=6, n_shared=1)
+    emap = np.array([0, 1, -1, 3], dtype=np.int32)
+    ids = np.array([[0, 1], [2, 3], [3, 3], [9, 0], [1, 2], [2, 2], [0, 3]], dtype=np.int32)
+    wts = rnd(44).uniform(0.1, 1.0, size=ids.shape).astype(np.float32)
+    got = oracle.forward_routed(spec, x, w13, w2, emap, ids, wts, shared_slots=[5], shared_range=(2, 5),
+                                identity_experts=True)
+    for t in range(spec.T):
+        coef = sum(float(wts[t, j]) for j in range(spec.k) if 0 <= ids[t, j] < spec.E and emap[ids[t, j]] >= 0)
+        coef += 1.0 if 2 <= t < 5 else 0.0
+        np.testing.assert_allclose(got[t], coef * x[t].astype(np.float64), rtol=1e-13, atol=1e-13)
+
+
+def test_routed_entry_with_own_routing_equals_the_gated_layer():
+    """Feeding the gate's own ids and (fp32-exact) weights back reproduces the gated layer."""
+    spec, x, wr, w13, w2 = small_layer(45, T=11, E=8, k=3, S=8)
+    emap = np.arange(8, dtype=np.int32)
+    ids, w, _ = oracle.route(spec, x, wr)
+    w32 = w.astype(np.float32)
+    full = oracle.forward(spec, x, wr, w13, w2, emap)
+    routed = oracle.forward_routed(spec, x, w13, w2, emap, ids, w32)
+    # only difference: the weights were rounded to fp32 on the way
+    np.testing.assert_allclose(routed, full, rtol=0, atol=2e-7 * np.abs(full).max())
+    sub = np.array([7, 2, 2, 10], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.forward_routed(spec, x, w13, w2, emap, ids, w32, tokens=sub), routed[sub])
