@@ -168,6 +168,26 @@ moe_status_t moe_forward(moe_layer_t *layer, const void *x, int32_t T,
                          int32_t shared_begin, int32_t shared_end,
                          void *out, void *hip_stream, uint32_t flags);
 
+/*
+ * The same pass for a rank that receives its tokens ALREADY ROUTED -- the input of an
+ * expert-parallel rank after the dispatch exchange (paper Sec. 2.1: tokens are routed
+ * to the devices that hold their experts): the gate is skipped.
+ *   topk_ids device [T,k] int32: logical expert ids per token; an id outside [0,E)
+ *            (e.g. -1) is an assignment that does not exist and contributes nothing;
+ *            ids whose map entry is -1 are skipped as in moe_forward; an id may repeat
+ *            within a token (it then counts once per occurrence).
+ *   topk_w   device [T,k] float: combine weights, used as given.
+ * Both are read in place during the pass (keep them unchanged until it has run on the
+ * stream) and never written.  Everything else (x, out, shared range, flags, errors,
+ * asynchrony, no allocation) as in moe_forward.  Afterwards moe_workspace_view's
+ * topk_ids/topk_w still name the workspace copies of the last GATED pass; all other
+ * intermediates are this pass's.
+ */
+moe_status_t moe_forward_routed(moe_layer_t *layer, const void *x, int32_t T,
+                                const int32_t *topk_ids, const float *topk_w,
+                                int32_t shared_begin, int32_t shared_end,
+                                void *out, void *hip_stream, uint32_t flags);
+
 /* Addresses of the intermediates (valid for the layer's lifetime). */
 moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *view);
 

@@ -37,7 +37,10 @@ __global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
     if (a < n_assign) {
         const int t = a / p.kk, j = a - t * p.kk;
         if (j < p.k) {
-            slot = p.map[p.ids[(size_t)t * p.k + j]];
+            // ids come from the gate, or from the caller when the routing is given: an id outside
+            // [0, E) is an assignment that does not exist
+            const int id = p.ids[(size_t)t * p.k + j];
+            slot = (unsigned)id < (unsigned)p.E ? p.map[id] : -1;
         } else if (t >= p.shared_begin && t < p.shared_end) {
             slot = p.map[p.E + (j - p.k)];
         }

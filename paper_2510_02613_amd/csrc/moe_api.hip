@@ -269,8 +269,9 @@ moe_status_t moe_workspace_view(const moe_layer_t *l, moe_workspace_view_t *v)
     return MOE_OK;
 }
 
-moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t shared_begin, int32_t shared_end,
-                         void *out, void *hip_stream, uint32_t flags)
+// One pass; routed_ids/routed_w non-NULL: the gate is skipped and the caller's routing is read in place.
+static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const int32_t *routed_ids, const float *routed_w,
+                                 int32_t shared_begin, int32_t shared_end, void *out, void *hip_stream, uint32_t flags)
 {
     if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
     const moe_config_t &c = l->cfg;
@@ -299,8 +300,9 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     p.w13 = l->buf.w13; p.w2 = l->buf.w2;
     p.map = (const int32_t *)(ws + l->lay.map[l->active]);
     p.logits = (float *)(ws + l->lay.logits);
-    p.ids = (int32_t *)(ws + l->lay.ids);
-    p.w = (float *)(ws + l->lay.w);
+    // the kernels after the gate only read ids and w
+    p.ids = routed_ids ? const_cast<int32_t *>(routed_ids) : (int32_t *)(ws + l->lay.ids);
+    p.w = routed_w ? const_cast<float *>(routed_w) : (float *)(ws + l->lay.w);
     p.slot_rank = (int32_t *)(ws + l->lay.slot_rank);
     p.blk_hist = (int32_t *)(ws + l->lay.blk_hist);
     p.counts = (int32_t *)(ws + l->lay.counts);
@@ -326,7 +328,7 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     hipError_t e = hipSuccess;
     auto mark = [&](int j) { if (ev && e == hipSuccess) e = hipEventRecord(ev[j], st); };
     mark(MOE_PHASE_GATE);
-    if (e == hipSuccess) e = launch_gate(p, st);
+    if (e == hipSuccess && !routed_ids) e = launch_gate(p, st);
     mark(MOE_PHASE_PERMUTE);
     if (e == hipSuccess) e = launch_permute(p, tile_rows, st);
     mark(MOE_PHASE_GEMM1);
@@ -346,6 +348,20 @@ moe_status_t moe_forward(moe_layer_t *l, const void *x, int32_t T, int32_t share
     if (e != hipSuccess) return fail(MOE_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
     if (ev) l->prof_count++;
     return MOE_OK;
+}
+
+moe_status_t moe_forward(moe_layer_t *layer, const void *x, int32_t T, int32_t shared_begin, int32_t shared_end,
+                         void *out, void *hip_stream, uint32_t flags)
+{
+    return forward_pass(layer, x, T, nullptr, nullptr, shared_begin, shared_end, out, hip_stream, flags);
+}
+
+moe_status_t moe_forward_routed(moe_layer_t *layer, const void *x, int32_t T, const int32_t *topk_ids, const float *topk_w,
+                                int32_t shared_begin, int32_t shared_end, void *out, void *hip_stream, uint32_t flags)
+{
+    if (T > 0 && (!topk_ids || !topk_w)) return fail(MOE_ERR_ARG, "topk_ids and topk_w must be non-NULL");
+    if (!aligned(topk_ids, 4) || !aligned(topk_w, 4)) return fail(MOE_ERR_ARG, "topk_ids and topk_w must be 4-byte aligned");
+    return forward_pass(layer, x, T, topk_ids, topk_w, shared_begin, shared_end, out, hip_stream, flags);
 }
 
 }  // extern "C"

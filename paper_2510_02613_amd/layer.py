@@ -98,6 +98,22 @@ class MoELayer:
                       int(shared_range[1]), s.cuda_stream, flags)
         return out
 
+    def forward_routed(self, x: torch.Tensor, topk_ids: torch.Tensor, topk_w: torch.Tensor,
+                       out: Optional[torch.Tensor] = None, shared_range=(0, 0), flags: int = 0,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """The pass with the routing given (device int32 ids [T,k], float32 weights [T,k]); no gate."""
+        assert x.dtype == self.elt and x.is_contiguous() and x.shape[1] == self.cfg.hidden
+        T = x.shape[0]
+        assert topk_ids.dtype == torch.int32 and topk_ids.is_contiguous() and tuple(topk_ids.shape) == (T, self.cfg.top_k)
+        assert topk_w.dtype == torch.float32 and topk_w.is_contiguous() and tuple(topk_w.shape) == (T, self.cfg.top_k)
+        assert topk_ids.device == x.device and topk_w.device == x.device
+        if out is None:
+            out = torch.empty_like(x)
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        B.moe_forward_routed(self.handle, x.data_ptr(), T, topk_ids.data_ptr(), topk_w.data_ptr(), out.data_ptr(),
+                             int(shared_range[0]), int(shared_range[1]), s.cuda_stream, flags)
+        return out
+
     # -- intermediates (tests) -------------------------------------------------
     def view(self, T: int) -> dict:
         """Host copies of the intermediates of the last forward over T tokens."""
