@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="qwen3_30b_a3b",
-                    help="qwen3_30b_a3b (headline) | dsv3_ep8_rank | dsv3_ep8_decode | qwen3_relayout | tiny_f32")
+                    help="qwen3_30b_a3b (headline) | dsv3_ep8_rank | dsv3_ep8_decode | qwen3_relayout | dsv2_lite | tiny_f32")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel events inside the timed region (roofline then is null)")

@@ -81,7 +81,7 @@ class MoELayer:
                        stream: Optional[torch.cuda.Stream] = None) -> None:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.moe_set_expert_map(self.handle, list(expert_map),
-                             None if not shared_slots else list(shared_slots), s.cuda_stream)
+                             None if shared_slots is None or len(shared_slots) == 0 else list(shared_slots), s.cuda_stream)
 
     # -- forward -------------------------------------------------------------
     def upload(self, x: np.ndarray) -> torch.Tensor:

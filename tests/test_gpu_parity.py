@@ -147,6 +147,11 @@ def test_dsv3_rank_full_size_sampled():
     _full_check(case, sample=64)
 
 
+def test_dsv2_lite_shape_full_size_sampled():
+    """third model shape of the paper's evaluation: 64 experts, top-6, no renormalisation, 2 shared experts"""
+    _full_check(_case(get_workload("dsv2_lite")), sample=64)
+
+
 def test_dsv3_decode_all_tokens():
     case = _case(get_workload("dsv3_ep8_decode"))
     _, v, _ = _full_check(case)

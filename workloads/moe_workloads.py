@@ -111,6 +111,13 @@ WORKLOADS: Dict[str, MoEWorkload] = {
         name="qwen3_relayout", tokens=4096, hidden=2048, inter=768, n_experts=128,
         top_k=8, n_slots=64, n_local=64, act_dtype="bf16", router_dtype="f32",
         gate="softmax", zipf_s=1.2, seed=5),
+    # beyond the five measured configs: the layer shape of the third model the paper serves
+    # (Sec. 5), DeepSeek-V2-Lite-like: 64 routed experts, top-6 without renormalisation, 2 shared experts
+    "dsv2_lite": MoEWorkload(
+        name="dsv2_lite", tokens=4096, hidden=2048, inter=1408, n_experts=64,
+        top_k=6, n_slots=66, n_local=64, act_dtype="bf16", router_dtype="f32",
+        gate="softmax", renormalize=False, routed_scale=1.0,
+        n_shared=2, shared_range=(0, 4096), seed=6),
 }
 
 
