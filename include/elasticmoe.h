@@ -151,6 +151,29 @@ moe_status_t moe_set_expert_map(moe_layer_t *layer, const int32_t *host_map, int
                                 const int32_t *host_shared_slots, void *hip_stream);
 
 /*
+ * Fill one slot of the weight pools in the background while forwards keep running
+ * (paper: new or migrated experts are copied into freshly mapped pages while the old
+ * instance serves, and only then the mapping is switched -- Sec. 3.2 "zero-downtime",
+ * Sec. 4.7 scale-up steps, p2p-copy in Sec. 4.6).  On one GPU the source is a device
+ * buffer the caller has staged (the landing buffer of a peer transfer).
+ *   slot        pool slot to fill; it must NOT be referenced by the active map
+ *               (MOE_ERR_MAP otherwise: forwards may be reading it)
+ *   src_w13     device [2I,H] act_dtype, 16-byte aligned     src_w2  device [H,I]
+ *   copy_stream stream the copy kernels run on               serve_stream  the stream
+ *               the forwards run on (must differ from copy_stream)
+ *   copy_blocks workgroups of the copy kernels (0 = 32): the throttle on how much HBM
+ *               bandwidth the fill may take from the forwards
+ * Ordering, all by events, no host synchronisation and no allocation: the copy starts
+ * after the work ALREADY enqueued on serve_stream (a forward that still reads the slot
+ * under an older map); the next moe_set_expert_map makes its stream wait for every
+ * fill issued since the previous switch, so forwards after that switch see the
+ * weights.  The weight pools given at moe_layer_create must be writable.  Forwards
+ * that run on other streams than serve_stream are the caller's to order.
+ */
+moe_status_t moe_load_expert(moe_layer_t *layer, int32_t slot, const void *src_w13, const void *src_w2,
+                             void *copy_stream, void *serve_stream, int32_t copy_blocks);
+
+/*
  * One forward pass of the layer, enqueued on `hip_stream` (a hipStream_t; NULL =
  * the default stream).  Asynchronous, never synchronises, never allocates.
  *   x    device [T,H] act_dtype, 16-byte aligned

@@ -23,7 +23,8 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_M
 # every symbol include/elasticmoe.h declares
 EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
-           "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed")
+           "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
+           "moe_load_expert")
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
 
@@ -80,6 +81,9 @@ def lib() -> ctypes.CDLL:
         L.moe_forward_routed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_uint32]
+        L.moe_load_expert.restype = ctypes.c_int
+        L.moe_load_expert.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
         L.moe_workspace_view.restype = ctypes.c_int
         L.moe_workspace_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(MoEWorkspaceView)]
         L.moe_layer_destroy.restype = None
@@ -147,6 +151,12 @@ def moe_forward_routed(layer, x_ptr: int, T: int, ids_ptr: int, w_ptr: int, out_
                        shared_begin: int = 0, shared_end: int = 0, stream: int = 0, flags: int = 0) -> None:
     _check(lib().moe_forward_routed(layer, ctypes.c_void_p(x_ptr), T, ctypes.c_void_p(ids_ptr), ctypes.c_void_p(w_ptr),
                                     shared_begin, shared_end, ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream), flags))
+
+
+def moe_load_expert(layer, slot: int, src_w13_ptr: int, src_w2_ptr: int, copy_stream: int, serve_stream: int,
+                    copy_blocks: int = 0) -> None:
+    _check(lib().moe_load_expert(layer, slot, ctypes.c_void_p(src_w13_ptr), ctypes.c_void_p(src_w2_ptr),
+                                 ctypes.c_void_p(copy_stream), ctypes.c_void_p(serve_stream), copy_blocks))
 
 
 def moe_workspace_view(layer) -> MoEWorkspaceView:

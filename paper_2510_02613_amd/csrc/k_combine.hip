@@ -66,7 +66,21 @@ __global__ void k_write_map(int32_t *dst, MapChunk c, int n)
     if (i < n) dst[i] = c.v[i];
 }
 
+// Plain device-to-device copy, 16 bytes per lane, grid-stride: the grid size is the caller's
+// throttle on how much HBM bandwidth a background slot fill may take from the forwards.
+__global__ __launch_bounds__(256) void k_copy16(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, int blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_copy16, dim3(blocks), dim3(256), 0, st, (uint4 *)dst, (const uint4 *)src, bytes / 16);
+    return hipGetLastError();
+}
 
 hipError_t launch_combine(const Pass &p, hipStream_t st)
 {

@@ -112,6 +112,10 @@ struct moe_layer {
     int active;      // which of the two device tables forwards read
     bool has_map;
     std::vector<int32_t> host_map;  // E + n_shared, copy of the active table
+    // slot fills that the next map switch has to wait for (one event per fill, reused after the switch)
+    std::vector<hipEvent_t> load_ev;
+    int n_pending = 0;
+    hipEvent_t serve_ev = nullptr;  // "work enqueued on the serving stream so far", recorded per fill
 };
 
 extern "C" {
@@ -175,6 +179,8 @@ void moe_layer_destroy(moe_layer_t *layer)
 {
     if (!layer) return;
     if (layer->prof_on) moe_profile_enable(layer, 0);
+    for (hipEvent_t ev : layer->load_ev) (void)hipEventDestroy(ev);
+    if (layer->serve_ev) (void)hipEventDestroy(layer->serve_ev);
     delete layer;
 }
 
@@ -245,11 +251,53 @@ moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t
     }
     const int target = l->has_map ? 1 - l->active : 0;
     int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map[target]);
-    hipError_t e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
+    hipError_t e = hipSuccess;
+    // slot fills enqueued by moe_load_expert: everything after this switch on hip_stream sees them complete
+    for (int i = 0; i < l->n_pending && e == hipSuccess; ++i) e = hipStreamWaitEvent((hipStream_t)hip_stream, l->load_ev[i], 0);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "waiting for slot fills failed: %s", hipGetErrorString(e));
+    l->n_pending = 0;
+    e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
     l->active = target;
     l->has_map = true;
     l->host_map.swap(table);
+    return MOE_OK;
+}
+
+moe_status_t moe_load_expert(moe_layer_t *l, int32_t slot, const void *src_w13, const void *src_w2,
+                             void *copy_stream, void *serve_stream, int32_t copy_blocks)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    const moe_config_t &c = l->cfg;
+    if (slot < 0 || slot >= c.n_slots) return fail(MOE_ERR_ARG, "slot %d is outside [0, %d)", slot, c.n_slots);
+    if (!src_w13 || !src_w2) return fail(MOE_ERR_ARG, "src_w13 and src_w2 must be non-NULL");
+    if (!aligned(src_w13, 16) || !aligned(src_w2, 16)) return fail(MOE_ERR_ARG, "src_w13 and src_w2 must be 16-byte aligned");
+    if (copy_blocks < 0 || copy_blocks > 65536) return fail(MOE_ERR_ARG, "copy_blocks %d is outside [0, 65536]", copy_blocks);
+    if (copy_stream == serve_stream) return fail(MOE_ERR_ARG, "copy_stream and serve_stream must differ (the fill is meant to run beside the forwards)");
+    if (l->has_map)
+        for (size_t e = 0; e < l->host_map.size(); ++e)
+            if (l->host_map[e] == slot)
+                return fail(MOE_ERR_MAP, "slot %d holds %s %d of the active map: it cannot be refilled while forwards may read it", slot,
+                            (int)e >= c.n_experts ? "shared expert" : "expert", (int)e >= c.n_experts ? (int)e - c.n_experts : (int)e);
+    hipError_t e = hipSuccess;
+    if (!l->serve_ev) e = hipEventCreateWithFlags(&l->serve_ev, hipEventDisableTiming);
+    if (e == hipSuccess && (int)l->load_ev.size() == l->n_pending) {
+        hipEvent_t ev = nullptr;
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e == hipSuccess) l->load_ev.push_back(ev);
+    }
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    // a forward already enqueued on the serving stream may still read the slot under an older map
+    e = hipEventRecord(l->serve_ev, (hipStream_t)serve_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent((hipStream_t)copy_stream, l->serve_ev, 0);
+    const size_t es = esize(c.act_dtype);
+    const size_t b13 = 2 * (size_t)c.inter * c.hidden * es, b2 = (size_t)c.hidden * c.inter * es;
+    const int blocks = copy_blocks ? copy_blocks : 32;
+    if (e == hipSuccess) e = launch_copy((char *)const_cast<void *>(l->buf.w13) + (size_t)slot * b13, src_w13, b13, blocks, (hipStream_t)copy_stream);
+    if (e == hipSuccess) e = launch_copy((char *)const_cast<void *>(l->buf.w2) + (size_t)slot * b2, src_w2, b2, blocks, (hipStream_t)copy_stream);
+    if (e == hipSuccess) e = hipEventRecord(l->load_ev[l->n_pending], (hipStream_t)copy_stream);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "slot fill failed: %s", hipGetErrorString(e));
+    l->n_pending++;
     return MOE_OK;
 }
 

@@ -76,6 +76,16 @@ class MoELayer:
         self.w13.copy_(_dev(w13_pool, self.device))
         self.w2.copy_(_dev(w2_pool, self.device))
 
+    def load_expert_async(self, slot: int, w13: torch.Tensor, w2: torch.Tensor, copy_stream: torch.cuda.Stream,
+                          serve_stream: Optional[torch.cuda.Stream] = None, copy_blocks: int = 0) -> None:
+        """Background fill of a slot that the active map does not use, from device tensors, on copy_stream;
+        the next set_expert_map waits for it."""
+        assert w13.dtype == self.elt and w13.is_contiguous() and tuple(w13.shape) == tuple(self.w13.shape[1:])
+        assert w2.dtype == self.elt and w2.is_contiguous() and tuple(w2.shape) == tuple(self.w2.shape[1:])
+        s = torch.cuda.current_stream(self.device) if serve_stream is None else serve_stream
+        B.moe_load_expert(self.handle, slot, w13.data_ptr(), w2.data_ptr(), copy_stream.cuda_stream, s.cuda_stream,
+                          copy_blocks)
+
     # -- placement -----------------------------------------------------------
     def set_expert_map(self, expert_map: Sequence[int], shared_slots: Optional[Sequence[int]] = None,
                        stream: Optional[torch.cuda.Stream] = None) -> None:

@@ -121,6 +121,33 @@ def test_expert_map_validation_is_all_or_nothing():
         B.moe_layer_destroy(h)
 
 
+def test_routed_forward_and_slot_fill_argument_checks():
+    """Everything these two entry points reject is rejected before anything is launched."""
+    cfg = good_cfg()
+    h = B.moe_layer_create(cfg, fake_buffers(cfg))
+    try:
+        with pytest.raises(B.MoEError) as ei:       # routing missing
+            B.moe_forward_routed(h, 0x50000, 4, 0, 0x70000, 0x60000)
+        assert ei.value.status == B.MOE_ERR_ARG
+        with pytest.raises(B.MoEError) as ei:       # same capacity rule as the gated pass
+            B.moe_forward_routed(h, 0x50000, 65, 0x70000, 0x80000, 0x60000)
+        assert ei.value.status == B.MOE_ERR_CAPACITY
+        with pytest.raises(B.MoEError) as ei:       # no map yet
+            B.moe_forward_routed(h, 0x50000, 4, 0x70000, 0x80000, 0x60000)
+        assert ei.value.status == B.MOE_ERR_MAP
+        for args in [(-1, 0x90000, 0xa0000, 1, 2, 0),     # slot below range
+                     (8, 0x90000, 0xa0000, 1, 2, 0),      # slot past the pool
+                     (3, 0, 0xa0000, 1, 2, 0),            # source missing
+                     (3, 0x90008, 0xa0000, 1, 2, 0),      # source not 16-byte aligned
+                     (3, 0x90000, 0xa0000, 1, 1, 0),      # copy stream == serving stream
+                     (3, 0x90000, 0xa0000, 1, 2, -5)]:    # negative throttle
+            with pytest.raises(B.MoEError) as ei:
+                B.moe_load_expert(h, *args)
+            assert ei.value.status == B.MOE_ERR_ARG, args
+    finally:
+        B.moe_layer_destroy(h)
+
+
 def test_valid_map_without_gpu_fails_cleanly_or_installs():
     import torch
     if torch.cuda.is_available():
