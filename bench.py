@@ -51,6 +51,10 @@ def parse_args():
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel events inside the timed region (roofline then is null)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--scale-while-serve", type=int, default=None, metavar="BLOCKS",
+                    help="qwen3_relayout only: after the timed region also time the phase-A layer idle, then with the 32 "
+                         "new experts being filled into free slots on a side stream by copy kernels of BLOCKS workgroups, "
+                         "then the phase-B layer after the switch")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measuring-stick kernels (sustained MFMA rate, streaming read) after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -197,12 +201,64 @@ def main():
         "roofline": roofline,
     }
 
+    if args.scale_while_serve is not None:
+        if wl.name != "qwen3_relayout":
+            print("bench.py: --scale-while-serve needs --workload qwen3_relayout", file=sys.stderr)
+            sys.exit(2)
+        result["scale_while_serve"] = scale_while_serve(torch, layer, wl, inp, x, out, stream, args)
+
     if not args.no_ceilings:
         result["ceilings"] = measure_ceilings(torch, B, layer, stream)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, args.cpu_seconds)
     print(json.dumps(result))
+
+
+def scale_while_serve(torch, layer, wl, inp, x, out, stream, args):
+    """Forward time of the phase-A layer (32 experts resident), the same while the other 32 experts are
+    copied into free slots on a side stream, and of the phase-B layer after the map switch."""
+    from workloads import relayout_maps
+    map_a, map_b = relayout_maps(wl)
+    copy = torch.cuda.Stream(device=x.device)
+    new = list(range(wl.n_slots // 2, wl.n_slots))
+    src = [(layer.upload(inp["w13_experts"][e]), layer.upload(inp["w2_experts"][e])) for e in new]
+    nbytes = sum(a.numel() * a.element_size() + b.numel() * b.element_size() for a, b in src)
+    layer.set_expert_map(map_a)
+
+    c0, c1, w0, w1 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+
+    def timed(n, fill):
+        for _ in range(3):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        torch.cuda.synchronize()
+        if fill:
+            # The whole set of new experts, enqueued first (this host thread needs ~0.1 ms per fill, and a
+            # serving loop that stops to issue them would be what is measured); the copies run on their
+            # stream while the forwards below are enqueued and run.
+            c0.record(copy)
+            for j, e in enumerate(new):
+                layer.load_expert_async(int(map_b[e]), src[j][0], src[j][1], copy, stream, copy_blocks=args.scale_while_serve)
+            c1.record(copy)
+        w0.record(stream)
+        for i in range(n):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        w1.record(stream)
+        torch.cuda.synchronize()
+        return w0.elapsed_time(w1) / n
+
+    n = 16
+    idle = timed(n, False)
+    busy = timed(n, True)
+    fill_ms = c0.elapsed_time(c1)
+    overlap_ms = max(0.0, min(w0.elapsed_time(c1), w0.elapsed_time(w1)))   # part of the forwards' window with copies running
+    layer.set_expert_map(map_b)              # waits (on the stream) for the fills
+    after = timed(n, False)
+    return {"copy_blocks": args.scale_while_serve, "forwards": n,
+            "ms_per_step_phase_a_idle": idle, "ms_per_step_phase_a_beside_fill": busy,
+            "window_ms": busy * n, "window_ms_with_copies_running": overlap_ms,
+            "fill_bytes": nbytes, "fill_ms": fill_ms, "fill_gbs": nbytes / (fill_ms * 1e-3) / 1e9,
+            "ms_per_step_phase_b_after_switch": after}
 
 
 def measure_ceilings(torch, B, layer, stream):
