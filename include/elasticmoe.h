@@ -115,6 +115,7 @@ typedef struct {
 /* moe_forward flags */
 #define MOE_FLAG_IDENTITY_EXPERTS 1u /* test mode: every expert returns its input row unchanged */
 #define MOE_FLAG_FORCE_GENERIC    2u /* run the plain (non-MFMA) expert kernels: debugging aid */
+#define MOE_FLAG_GATE_TILED       4u /* bf16 activations: use the LDS-tiled gate logits kernel at any batch size (testing aid) */
 
 /*
  * Bytes of device workspace a layer of this configuration needs (0 if cfg is

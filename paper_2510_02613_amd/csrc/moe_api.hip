@@ -327,7 +327,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     if (T > c.max_tokens) return fail(MOE_ERR_CAPACITY, "T %d exceeds max_tokens %d", T, c.max_tokens);
     if (shared_begin < 0 || shared_begin > shared_end || shared_end > T)
         return fail(MOE_ERR_ARG, "shared range [%d,%d) is not inside [0,%d]", shared_begin, shared_end, T);
-    if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
+    if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC | MOE_FLAG_GATE_TILED)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
     if (!l->has_map) return fail(MOE_ERR_MAP, "no expert map installed: call moe_set_expert_map first");
     if (T == 0) return MOE_OK;
     if (!x || !out) return fail(MOE_ERR_ARG, "x and out must be non-NULL");
@@ -362,6 +362,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.h = ws + l->lay.h;
     p.y = ws + l->lay.y;
 
+    p.gate_tiled = (flags & MOE_FLAG_GATE_TILED) != 0;
     const bool identity = flags & MOE_FLAG_IDENTITY_EXPERTS;
     const bool mfma = p.act_bf16 && !(flags & MOE_FLAG_FORCE_GENERIC);
     // large tiles once groups average at least a few MFMA tiles of rows

@@ -49,6 +49,7 @@ struct Pass {
     void *h;             // [A,I]
     void *y;             // [A,H]
     int32_t max_tiles;
+    int32_t gate_tiled;  // the LDS-tiled gate logits kernel is forced (testing aid)
 };
 
 constexpr int kAssignPerBlock = 1024;  // assignments ranked by one block of the slot histogram kernel

@@ -232,3 +232,23 @@ def test_weight_streaming_kernels_small_shapes(tokens):
     case = _case(wl)
     _, v, _ = _full_check(case)
     assert (v["counts"] == 0).any()
+
+
+@pytest.mark.parametrize("tokens", [300, 1000])
+@pytest.mark.parametrize("router", ["f32", "bf16"])
+def test_tiled_gate_kernel_small_shapes(tokens, router):
+    """The LDS-tiled gate logits kernel (chosen by itself only for large batches) on ragged small ones:
+    partial token blocks, fp32 router split into bf16 planes and bf16 router."""
+    from paper_2510_02613_amd.binding import MOE_FLAG_GATE_TILED
+    wl = MoEWorkload(name="tiled_gate", tokens=tokens, **{**SMALL, "router_dtype": router, "n_experts": 80, "n_slots": 80,
+                                                           "n_local": 80, "seed": 16})
+    _full_check(_case(wl), flags=MOE_FLAG_GATE_TILED)
+
+
+def test_tiled_gate_kernel_grouped_sigmoid():
+    from paper_2510_02613_amd.binding import MOE_FLAG_GATE_TILED
+    wl = MoEWorkload(name="tiled_gate_g", tokens=700, hidden=256, inter=136, n_experts=160, top_k=4,
+                     n_slots=21, n_local=20, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=8, topk_group=3, routed_scale=2.5, n_shared=1,
+                     shared_range=(0, 700), seed=17)
+    _full_check(_case(wl), flags=MOE_FLAG_GATE_TILED)
