@@ -55,6 +55,9 @@ def parse_args():
                     help="qwen3_relayout only: after the timed region also time the phase-A layer idle, then with the 32 "
                          "new experts being filled into free slots on a side stream by copy kernels of BLOCKS workgroups, "
                          "then the phase-B layer after the switch")
+    ap.add_argument("--virtual-pool", action="store_true",
+                    help="back the two weight pools with contiguous virtual tensors over separately allocated physical "
+                         "pages (moe_vpool_*), pages mapped in a shuffled order, instead of plain allocations")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measuring-stick kernels (sustained MFMA rate, streaming read) after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -120,11 +123,22 @@ def main():
     else:
         expert_map = block_expert_map(wl.n_experts, 0, wl.n_local)
     shared = shared_slots_of(wl)
+    pools = {}
+    if args.virtual_pool:
+        from paper_2510_02613_amd.layer import VirtualPool
+        elt = torch.int16 if wl.act_dtype == "bf16" else torch.float32
+        pools = {"w13_pool": VirtualPool(wl.n_slots, (2 * wl.inter, wl.hidden), elt, dev),
+                 "w2_pool": VirtualPool(wl.n_slots, (wl.hidden, wl.inter), elt, dev)}
+        order = np.random.Generator(np.random.PCG64(7)).permutation(wl.n_slots)
+        for pool in pools.values():
+            pages = [pool.page_alloc() for _ in range(wl.n_slots)]
+            for s in range(wl.n_slots):
+                pool.map(s, pages[int(order[s])])
     layer = MoELayer(hidden=wl.hidden, inter=wl.inter, n_experts=wl.n_experts, top_k=wl.top_k,
                      n_slots=wl.n_slots, max_tokens=wl.tokens, act_dtype=wl.act_dtype,
                      router_dtype=wl.router_dtype, gate=wl.gate, n_group=wl.n_group,
                      topk_group=wl.topk_group, renormalize=wl.renormalize, routed_scale=wl.routed_scale,
-                     n_shared=wl.n_shared, router_w=inp["router_w"], logit_bias=inp["logit_bias"], device=dev)
+                     n_shared=wl.n_shared, router_w=inp["router_w"], logit_bias=inp["logit_bias"], device=dev, **pools)
     w13_pool = build_slot_pool(inp["w13_experts"], expert_map, wl.n_slots, wl.n_local, shared)
     w2_pool = build_slot_pool(inp["w2_experts"], expert_map, wl.n_slots, wl.n_local, shared)
     layer.load_pool(w13_pool, w2_pool)
@@ -196,7 +210,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.act_dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
+        "config": {"workload": wl.name, "weight_pools": "virtual (moe_vpool)" if args.virtual_pool else "plain", "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
                    "n_experts": wl.n_experts, "top_k": wl.top_k, "local_slots": int((expert_map >= 0).sum()) + wl.n_shared,
                    "gate": wl.gate, "assignments": work["assignments"], "active_slots": work["active_slots"],
                    "rows_per_slot_max": int(counts.max()), "rows_per_slot_mean": float(counts[counts > 0].mean()) if (counts > 0).any() else 0.0},
@@ -220,6 +234,11 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, args.cpu_seconds)
     print(json.dumps(result))
+    if pools:
+        torch.cuda.synchronize()
+        layer.close()
+        for pool in pools.values():
+            pool.close()
 
 
 def scale_while_serve(torch, layer, wl, inp, x, out, stream, args):

@@ -44,6 +44,7 @@ extern "C" {
 #endif
 
 typedef struct moe_layer moe_layer_t; /* opaque host object */
+typedef struct moe_vpool moe_vpool_t; /* opaque host object: a weight pool as a contiguous virtual tensor */
 
 typedef enum {
     MOE_OK = 0,
@@ -247,6 +248,35 @@ moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
 moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, int32_t random_operands, float *sink,
                               void *hip_stream, double *flops);
 moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void *hip_stream);
+
+/*
+ * A weight pool as ONE contiguous virtual tensor over separately allocated physical pages
+ * (paper: Virtual Expert Management, Sec. 3.2; the vpage-remap primitive, Sec. 4.6 / App. D):
+ * kernels see slots 0..n-1 back to back at moe_vpool_base(), slot_bytes apart, and which
+ * physical page lies under a slot is changed in O(1) without moving a byte -- map a fresh
+ * page behind the resident ones to grow, exchange the pages under two slots to re-place
+ * experts, unmap and free pages to shrink.  A layer uses such a pool by being given its base
+ * as moe_buffers_t.w13 / .w2 (one pool each); the expert map then names VIRTUAL slots and an
+ * identity map is all that kernels written for contiguous experts need.
+ *   moe_vpool_create      reserves the address range only (slot_bytes must be a multiple of
+ *                         the device's mapping granularity, MOE_ERR_UNSUPPORTED otherwise).
+ *   moe_vpool_page_alloc  allocates one slot-sized physical page; *page = its id.
+ *   moe_vpool_map         puts a page under a slot (both must be free: MOE_ERR_MAP), read/write.
+ *   moe_vpool_unmap       takes the page from under a slot; the page keeps its contents.
+ *   moe_vpool_page_free   releases an unmapped page.       moe_vpool_page_of  page under a slot, or -1.
+ *   moe_vpool_destroy     unmaps and releases everything and frees the address range.
+ * These are the only calls of the library that own device memory.  Mapping calls are host
+ * operations, not stream ordered: unmap a slot only when no kernel that can read it is in
+ * flight, and never let an expert map name a slot that has no page (reading it faults).
+ */
+moe_status_t moe_vpool_create(size_t slot_bytes, int32_t n_vslots, moe_vpool_t **out);
+void *moe_vpool_base(const moe_vpool_t *pool);
+moe_status_t moe_vpool_page_alloc(moe_vpool_t *pool, int32_t *page);
+moe_status_t moe_vpool_page_free(moe_vpool_t *pool, int32_t page);
+moe_status_t moe_vpool_map(moe_vpool_t *pool, int32_t vslot, int32_t page);
+moe_status_t moe_vpool_unmap(moe_vpool_t *pool, int32_t vslot);
+int32_t moe_vpool_page_of(const moe_vpool_t *pool, int32_t vslot);
+moe_status_t moe_vpool_destroy(moe_vpool_t *pool);
 
 /* Frees the host object only (the library owns no device memory). NULL is allowed. */
 void moe_layer_destroy(moe_layer_t *layer);

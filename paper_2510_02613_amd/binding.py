@@ -24,7 +24,8 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_M
 EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
-           "moe_load_expert")
+           "moe_load_expert", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
+           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy")
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
 
@@ -84,6 +85,21 @@ def lib() -> ctypes.CDLL:
         L.moe_load_expert.restype = ctypes.c_int
         L.moe_load_expert.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
+        L.moe_vpool_create.restype = ctypes.c_int
+        L.moe_vpool_create.argtypes = [ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
+        L.moe_vpool_base.restype = ctypes.c_void_p
+        L.moe_vpool_base.argtypes = [ctypes.c_void_p]
+        L.moe_vpool_page_alloc.restype = ctypes.c_int
+        L.moe_vpool_page_alloc.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)]
+        for name in ("moe_vpool_page_free", "moe_vpool_unmap"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        L.moe_vpool_map.restype = ctypes.c_int
+        L.moe_vpool_map.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32]
+        L.moe_vpool_page_of.restype = ctypes.c_int32
+        L.moe_vpool_page_of.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        L.moe_vpool_destroy.restype = ctypes.c_int
+        L.moe_vpool_destroy.argtypes = [ctypes.c_void_p]
         L.moe_workspace_view.restype = ctypes.c_int
         L.moe_workspace_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(MoEWorkspaceView)]
         L.moe_layer_destroy.restype = None
@@ -157,6 +173,42 @@ def moe_load_expert(layer, slot: int, src_w13_ptr: int, src_w2_ptr: int, copy_st
                     copy_blocks: int = 0) -> None:
     _check(lib().moe_load_expert(layer, slot, ctypes.c_void_p(src_w13_ptr), ctypes.c_void_p(src_w2_ptr),
                                  ctypes.c_void_p(copy_stream), ctypes.c_void_p(serve_stream), copy_blocks))
+
+
+def moe_vpool_create(slot_bytes: int, n_vslots: int):
+    h = ctypes.c_void_p()
+    _check(lib().moe_vpool_create(ctypes.c_size_t(slot_bytes), n_vslots, ctypes.byref(h)))
+    return h
+
+
+def moe_vpool_base(pool) -> int:
+    return int(lib().moe_vpool_base(pool) or 0)
+
+
+def moe_vpool_page_alloc(pool) -> int:
+    page = ctypes.c_int32(-1)
+    _check(lib().moe_vpool_page_alloc(pool, ctypes.byref(page)))
+    return int(page.value)
+
+
+def moe_vpool_page_free(pool, page: int) -> None:
+    _check(lib().moe_vpool_page_free(pool, page))
+
+
+def moe_vpool_map(pool, vslot: int, page: int) -> None:
+    _check(lib().moe_vpool_map(pool, vslot, page))
+
+
+def moe_vpool_unmap(pool, vslot: int) -> None:
+    _check(lib().moe_vpool_unmap(pool, vslot))
+
+
+def moe_vpool_page_of(pool, vslot: int) -> int:
+    return int(lib().moe_vpool_page_of(pool, vslot))
+
+
+def moe_vpool_destroy(pool) -> None:
+    _check(lib().moe_vpool_destroy(pool))
 
 
 def moe_workspace_view(layer) -> MoEWorkspaceView:

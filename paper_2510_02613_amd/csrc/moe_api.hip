@@ -16,14 +16,25 @@
 using namespace emoe;
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
+
+namespace emoe {
+// the message moe_last_error() returns on this thread (shared by every translation unit of the library)
+moe_status_t set_error(moe_status_t st, const char *fmt, va_list ap)
+{
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    return st;
+}
+}  // namespace emoe
+
+namespace {
 
 moe_status_t fail(moe_status_t st, const char *fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    set_error(st, fmt, ap);
     va_end(ap);
     return st;
 }

@@ -21,6 +21,51 @@ def _dev(a: np.ndarray, device) -> torch.Tensor:
     return torch.from_numpy(a).to(device)
 
 
+class _DeviceSpan:
+    """Names a span of device memory for torch.as_tensor (no copy, no ownership)."""
+
+    def __init__(self, ptr: int, shape, typestr: str):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (ptr, False), "version": 2}
+
+
+class VirtualPool:
+    """A weight pool as one contiguous virtual tensor [n_vslots, *slot_shape] over separately
+    allocated physical pages (the library's moe_vpool_* calls).  `tensor` is a torch view of the
+    whole virtual range: index it only at slots that have a page."""
+
+    def __init__(self, n_vslots: int, slot_shape, elt: torch.dtype, device="cuda:0"):
+        self.device = torch.device(device)
+        self.n_vslots, self.slot_shape, self.elt = n_vslots, tuple(slot_shape), elt
+        esize = torch.empty((), dtype=elt).element_size()
+        self.slot_bytes = int(np.prod(self.slot_shape)) * esize
+        with torch.cuda.device(self.device):
+            self.handle = B.moe_vpool_create(self.slot_bytes, n_vslots)
+        typestr = {torch.int16: "<i2", torch.float32: "<f4"}[elt]
+        self.tensor = torch.as_tensor(_DeviceSpan(B.moe_vpool_base(self.handle), (n_vslots,) + self.slot_shape, typestr),
+                                      device=self.device)
+
+    def page_alloc(self) -> int:
+        return B.moe_vpool_page_alloc(self.handle)
+
+    def page_free(self, page: int) -> None:
+        B.moe_vpool_page_free(self.handle, page)
+
+    def map(self, vslot: int, page: int) -> None:
+        B.moe_vpool_map(self.handle, vslot, page)
+
+    def unmap(self, vslot: int) -> None:
+        B.moe_vpool_unmap(self.handle, vslot)
+
+    def page_of(self, vslot: int) -> int:
+        return B.moe_vpool_page_of(self.handle, vslot)
+
+    def close(self) -> None:
+        if getattr(self, "handle", None) is not None:
+            self.tensor = None
+            B.moe_vpool_destroy(self.handle)
+            self.handle = None
+
+
 class MoELayer:
     """One layer over caller-visible torch buffers.
 
@@ -31,7 +76,8 @@ class MoELayer:
     def __init__(self, *, hidden, inter, n_experts, top_k, n_slots, max_tokens, act_dtype="bf16",
                  router_dtype="f32", gate="softmax", n_group=1, topk_group=1, renormalize=True,
                  routed_scale=1.0, n_shared=0, router_w: np.ndarray, logit_bias=None,
-                 select_bias=None, device="cuda:0"):
+                 select_bias=None, device="cuda:0", w13_pool: Optional[VirtualPool] = None,
+                 w2_pool: Optional[VirtualPool] = None):
         self.device = torch.device(device)
         dt = {"f32": B.MOE_F32, "bf16": B.MOE_BF16}
         self.cfg = B.MoEConfig(hidden, inter, n_experts, top_k, n_slots, max_tokens, dt[act_dtype],
@@ -43,8 +89,17 @@ class MoELayer:
         self.router_w = _dev(router_w, self.device)
         self.logit_bias = None if logit_bias is None else _dev(np.asarray(logit_bias, np.float32), self.device)
         self.select_bias = None if select_bias is None else _dev(np.asarray(select_bias, np.float32), self.device)
-        self.w13 = torch.empty((n_slots, 2 * inter, hidden), dtype=self.elt, device=self.device)
-        self.w2 = torch.empty((n_slots, hidden, inter), dtype=self.elt, device=self.device)
+        # the pools: plain allocations, or views of virtual pools the caller maps pages under
+        if w13_pool is None:
+            self.w13 = torch.empty((n_slots, 2 * inter, hidden), dtype=self.elt, device=self.device)
+        else:
+            assert w13_pool.n_vslots == n_slots and w13_pool.slot_shape == (2 * inter, hidden) and w13_pool.elt == self.elt
+            self.w13 = w13_pool.tensor
+        if w2_pool is None:
+            self.w2 = torch.empty((n_slots, hidden, inter), dtype=self.elt, device=self.device)
+        else:
+            assert w2_pool.n_vslots == n_slots and w2_pool.slot_shape == (hidden, inter) and w2_pool.elt == self.elt
+            self.w2 = w2_pool.tensor
         ws_bytes = B.moe_workspace_bytes(self.cfg)
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
         self.buf = B.MoEBuffers(self.router_w.data_ptr(),

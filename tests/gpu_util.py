@@ -29,7 +29,9 @@ class Case:
     """A workload instantiated on the GPU plus everything the oracle needs."""
 
     def __init__(self, wl: MoEWorkload, expert_map=None, shared_slots=None, inputs=None,
-                 select_bias=None, max_tokens=None):
+                 select_bias=None, max_tokens=None, pools=None):
+        """pools = (w13 VirtualPool, w2 VirtualPool): the layer runs on those instead of plain allocations;
+        then only the slots the placement uses are uploaded (the others may have no page under them)."""
         from paper_2510_02613_amd.layer import MoELayer
         self.wl = wl
         self.inp = make_inputs(wl) if inputs is None else inputs
@@ -44,8 +46,13 @@ class Case:
                               n_group=wl.n_group, topk_group=wl.topk_group, renormalize=wl.renormalize,
                               routed_scale=wl.routed_scale, n_shared=wl.n_shared,
                               router_w=self.inp["router_w"], logit_bias=self.inp["logit_bias"],
-                              select_bias=select_bias)
-        self.place(self.expert_map, self.shared_slots)
+                              select_bias=select_bias, **({} if pools is None else dict(w13_pool=pools[0], w2_pool=pools[1])))
+        if pools is None:
+            self.place(self.expert_map, self.shared_slots)
+        else:
+            self.place(self.expert_map, self.shared_slots, upload=False)
+            for s in sorted(set(int(v) for v in self.expert_map if v >= 0) | set(int(v) for v in self.shared_slots[:wl.n_shared])):
+                self.layer.load_slot(s, self.w13_pool[s], self.w2_pool[s])
         self.x_dev = self.layer.upload(self.inp["x"])
 
     def place(self, expert_map, shared_slots=None, upload=True):

@@ -1,0 +1,127 @@
+"""The weight pools as contiguous virtual tensors over physical pages (moe_vpool_*): growth by mapping
+fresh pages behind the resident ones, re-placement of experts by exchanging pages (no byte moves),
+shrink -- each checked against the oracle or for bit-identical outputs."""
+import numpy as np
+import pytest
+
+from workloads import MoEWorkload
+
+pytestmark = pytest.mark.gpu
+
+MID = dict(hidden=512, inter=264, n_experts=32, top_k=4, n_slots=16, n_local=16,
+           act_dtype="bf16", router_dtype="f32", gate="softmax", seed=41)
+
+
+def _check(case):
+    from gpu_util import check_routing, check_bookkeeping, check_output
+    wl = case.wl
+    out = case.run()
+    v = case.layer.view(wl.tokens)
+    ids, _, _ = check_routing(case, v["topk_ids"], v["topk_w"])
+    check_bookkeeping(case, v, wl.tokens, wl.shared_range)
+    check_output(case, out, ids)
+    return out
+
+
+def test_virtual_pool_grow_replace_shrink():
+    import torch
+    from gpu_util import Case, tensor_to_host
+    from paper_2510_02613_amd.layer import VirtualPool
+    wl = MoEWorkload(name="vpool", tokens=900, **MID)
+    H, I, S = wl.hidden, wl.inter, wl.n_slots
+    p13 = VirtualPool(S, (2 * I, H), torch.int16)
+    p2 = VirtualPool(S, (H, I), torch.int16)
+    try:
+        # 8 resident experts: pages allocated in one order, mapped under slots 0..7 in another
+        pages13 = [p13.page_alloc() for _ in range(8)]
+        pages2 = [p2.page_alloc() for _ in range(8)]
+        for s in range(8):
+            p13.map(s, pages13[7 - s])
+            p2.map(s, pages2[(s + 3) % 8])
+        map_a = np.full(wl.n_experts, -1, np.int32)
+        map_a[:8] = np.arange(8)
+        case = Case(wl, expert_map=map_a, pools=(p13, p2))
+        assert case.layer.w13.data_ptr() == p13.tensor.data_ptr()
+        out_a = _check(case)
+
+        # grow: fresh pages mapped behind the resident ones, filled in the background, then the switch
+        base = (p13.tensor.data_ptr(), p2.tensor.data_ptr())
+        for s in range(8, 16):
+            p13.map(s, p13.page_alloc())
+            p2.map(s, p2.page_alloc())
+        copy = torch.cuda.Stream()
+        src = [(case.layer.upload(case.inp["w13_experts"][e]), case.layer.upload(case.inp["w2_experts"][e])) for e in range(8, 16)]
+        for e in range(8, 16):
+            case.layer.load_expert_async(e, src[e - 8][0], src[e - 8][1], copy)
+        map_b = map_a.copy()
+        map_b[8:16] = np.arange(8, 16)                 # contiguous: expert e in virtual slot e
+        case.place(map_b, upload=False)
+        assert base == (case.layer.w13.data_ptr(), case.layer.w2.data_ptr())
+        out_b = _check(case)
+        np.testing.assert_array_equal(tensor_to_host(p13.tensor[:16]), case.w13_pool)
+
+        # re-place without moving a byte: exchange the pages under slots 3 and 12, and the map entries
+        torch.cuda.synchronize()
+        for pool in (p13, p2):
+            a, b = pool.page_of(3), pool.page_of(12)
+            pool.unmap(3)
+            pool.unmap(12)
+            pool.map(3, b)
+            pool.map(12, a)
+        np.testing.assert_array_equal(tensor_to_host(p13.tensor[3]), case.inp["w13_experts"][12])
+        np.testing.assert_array_equal(tensor_to_host(p2.tensor[12]), case.inp["w2_experts"][3])
+        map_c = map_b.copy()
+        map_c[3], map_c[12] = 12, 3
+        case.place(map_c, upload=False)
+        out_c = _check(case)
+        np.testing.assert_array_equal(out_c, out_b)     # same experts, same weights, same sums
+
+        # shrink back to the first 8 experts: expert 3 now lives under slot 12, so it stays; slot 3 (expert 12) goes
+        map_d = map_a.copy()
+        map_d[3] = 12
+        case.place(map_d, upload=False)
+        out_d = case.run()
+        np.testing.assert_array_equal(out_d, out_a)
+        torch.cuda.synchronize()
+        for s in [3, 8, 9, 10, 11, 13, 14, 15]:
+            for pool in (p13, p2):
+                page = pool.page_of(s)
+                pool.unmap(s)
+                pool.page_free(page)
+        np.testing.assert_array_equal(case.run(), out_a)   # the remaining pages are untouched
+        case.layer.close()
+    finally:
+        torch.cuda.synchronize()
+        p13.close()
+        p2.close()
+
+
+def test_virtual_pool_bookkeeping_errors():
+    import torch
+    from paper_2510_02613_amd import binding as B
+    from paper_2510_02613_amd.layer import VirtualPool
+    with pytest.raises(B.MoEError) as ei:
+        B.moe_vpool_create(4096 + 16, 4)               # slots could not lie back to back
+    assert ei.value.status == B.MOE_ERR_UNSUPPORTED
+    pool = VirtualPool(4, (64, 64), torch.float32)      # 16 KB slots
+    try:
+        a, b = pool.page_alloc(), pool.page_alloc()
+        pool.map(0, a)
+        assert pool.page_of(0) == a and pool.page_of(1) == -1
+        for call in (lambda: pool.map(0, b),            # slot taken
+                     lambda: pool.map(1, a),            # page taken
+                     lambda: pool.page_free(a),         # still mapped
+                     lambda: pool.unmap(2)):            # nothing there
+            with pytest.raises(B.MoEError) as ei:
+                call()
+            assert ei.value.status == B.MOE_ERR_MAP
+        with pytest.raises(B.MoEError):
+            pool.map(4, b)
+        pool.tensor[0].fill_(1.5)
+        pool.unmap(0)
+        pool.map(3, a)                                  # the page keeps its contents
+        torch.cuda.synchronize()
+        assert float(pool.tensor[3].min()) == 1.5 and float(pool.tensor[3].max()) == 1.5
+        pool.page_free(b)
+    finally:
+        pool.close()
