@@ -174,3 +174,19 @@ def test_workloads_are_seeded_and_reproducible():
             np.testing.assert_array_equal(a[k], b[k])
     assert a["x"].shape == (64, 128) and a["w13_experts"].shape == (8, 128, 128)
     assert abs(float(a["w2_experts"].std()) - 0.02) < 2e-3
+
+
+def test_virtual_pool_argument_checks_and_no_gpu():
+    with pytest.raises(B.MoEError) as ei:
+        B.moe_vpool_create(0, 4)
+    assert ei.value.status == B.MOE_ERR_ARG
+    with pytest.raises(B.MoEError) as ei:
+        B.moe_vpool_create(4096, 0)
+    assert ei.value.status == B.MOE_ERR_ARG
+    assert B.moe_vpool_base(None) == 0 and B.moe_vpool_page_of(None, 0) == -1
+    B.moe_vpool_destroy(None)
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(B.MoEError) as ei:      # no device: nothing to reserve addresses on
+            B.moe_vpool_create(4096, 4)
+        assert ei.value.status in (B.MOE_ERR_HIP, B.MOE_ERR_UNSUPPORTED)
