@@ -55,6 +55,8 @@ def parse_args():
                     help="qwen3_relayout only: after the timed region also time the phase-A layer idle, then with the 32 "
                          "new experts being filled into free slots on a side stream by copy kernels of BLOCKS workgroups, "
                          "then the phase-B layer after the switch")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one forward into a HIP graph and time replays of it (no per-kernel events, so no roofline)")
     ap.add_argument("--virtual-pool", action="store_true",
                     help="back the two weight pools with contiguous virtual tensors over separately allocated physical "
                          "pages (moe_vpool_*), pages mapped in a shuffled order, instead of plain allocations")
@@ -153,7 +155,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    use_events = not args.no_phase_events
+    if args.hip_graph:
+        side = torch.cuda.Stream(device=dev)
+        with torch.cuda.stream(side):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=side)
+        step = graph.replay
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+    use_events = not args.no_phase_events and not args.hip_graph
     if use_events:
         B.moe_profile_enable(layer.handle, True)
         step()  # events exist now; keep their first use out of the timed region
@@ -210,7 +224,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.act_dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "weight_pools": "virtual (moe_vpool)" if args.virtual_pool else "plain", "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
+        "config": {"workload": wl.name, "weight_pools": "virtual (moe_vpool)" if args.virtual_pool else "plain",
+                   "launch": "hip graph replay" if args.hip_graph else "eager", "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
                    "n_experts": wl.n_experts, "top_k": wl.top_k, "local_slots": int((expert_map >= 0).sum()) + wl.n_shared,
                    "gate": wl.gate, "assignments": work["assignments"], "active_slots": work["active_slots"],
                    "rows_per_slot_max": int(counts.max()), "rows_per_slot_mean": float(counts[counts > 0].mean()) if (counts > 0).any() else 0.0},
