@@ -293,14 +293,25 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     constexpr int BNO = kFirst ? kBN / 2 : kBN;        // output columns per workgroup
     const int n_ntiles = (N + BNO - 1) / BNO;
 
-    const int total = *p.n_tiles * n_ntiles;
-    const int per_xcd = (total + kXcds - 1) / kXcds;
+    // Work is dealt to the 8 XCDs in UNITS: a chunk of the (size-ordered) tile list with a run of its
+    // N-slices.  Unit u belongs to XCD u % 8 -- largest chunks first on every XCD, loads equal to
+    // within one unit -- and workgroup ids are dealt round-robin to the XCDs by the hardware, so
+    // workgroup b works for XCD b % 8 and takes that XCD's units in order, the N-slices of a unit
+    // on consecutive workgroups (they share the chunk's token rows in that XCD's L2).  A chunk is
+    // one unit when there are enough chunks to balance the XCDs (16 units each); otherwise its
+    // N-slices are split into g equal runs, g the smallest divisor that gives enough units.
+    const int n_chunks = *p.n_tiles;
+    int g = n_ntiles;
+    for (int d = 1; d < n_ntiles; ++d)
+        if (n_ntiles % d == 0 && n_chunks * d >= 16 * kXcds) { g = d; break; }
+    const int spp = n_ntiles / g;                      // N-slices per unit
     const int b = blockIdx.x;
-    if (b / kXcds >= per_xcd) return;
-    const int lid = (b % kXcds) * per_xcd + b / kXcds;
-    if (lid >= total) return;
-    const MTile mt = p.tiles[lid / n_ntiles];
-    const int n0 = (lid % n_ntiles) * BNO;
+    const int j = b / kXcds;
+    const int unit = (j / spp) * kXcds + b % kXcds;
+    const int chunk = unit / g;
+    if (chunk >= n_chunks) return;
+    const MTile mt = p.tiles[chunk];
+    const int n0 = ((unit % g) * spp + j % spp) * BNO;
 
     __shared__ __attribute__((aligned(1024))) char ring[kLdsBytes];
     WaveCtx c;
@@ -384,11 +395,11 @@ hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st)
 {
     if (which == 0) {
         const int nt = (p.I + kBN / 2 - 1) / (kBN / 2);
-        const int grid = (p.max_tiles * nt + kXcds - 1) / kXcds * kXcds;
+        const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
         hipLaunchKernelGGL((k_expert_gemm_mfma8<true>), dim3(grid), dim3(kThreads), 0, st, p);
     } else {
         const int nt = (p.H + kBN - 1) / kBN;
-        const int grid = (p.max_tiles * nt + kXcds - 1) / kXcds * kXcds;
+        const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
         hipLaunchKernelGGL((k_expert_gemm_mfma8<false>), dim3(grid), dim3(kThreads), 0, st, p);
     }
     return hipGetLastError();

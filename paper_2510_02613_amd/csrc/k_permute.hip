@@ -90,9 +90,18 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int32_t *scratch, int
     return base + incl - v;
 }
 
-__global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, int tile_rows)
+constexpr int kSortMax = 2048;   // tile lists up to this long can be ordered by size (staged in LDS)
+constexpr int kSizeBins = 12;    // size classes: 32-row token tiles of a chunk, capped (even, scanned in pairs)
+
+// sort_tiles != 0: the tile list is left ordered by size class, largest first, ties in slot
+// order (longest-processing-time-first: the tail of a launch that is only a few rounds of the
+// chip deep then consists of the cheapest tiles).  Lists longer than kSortMax stay in slot order.
+__global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, int tile_rows, int sort_tiles)
 {
     __shared__ int32_t scratch[8];
+    __shared__ MTile staged[kSortMax];
+    __shared__ int32_t bin_cnt[kSizeBins][kThreads + 1];
+    const bool staging = sort_tiles && p.max_tiles <= kSortMax;
     const int tid = threadIdx.x;
     const int S = p.S;
     // 1. per slot: running sum over blocks (blk_hist becomes the block's exclusive base)
@@ -131,7 +140,8 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
                     mt.row_begin = row_off + i * per;
                     mt.rows = max(0, min(per, c - i * per));
                     mt.pad = 0;
-                    p.tiles[idx] = mt;
+                    if (staging) staged[idx] = mt;
+                    else         p.tiles[idx] = mt;
                 }
             }
         }
@@ -141,6 +151,39 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
     if (tid == 0) {
         p.offs[S] = row_carry;
         *p.n_tiles = min(tile_carry, p.max_tiles);
+    }
+    if (!staging) return;
+    // 3. stable counting sort of the staged list by size class, descending.  Thread t owns the
+    // contiguous index range [t*per_thread, (t+1)*per_thread): counts per (class, thread), an
+    // exclusive scan over (class descending, thread ascending), then placement in index order.
+    __syncthreads();
+    const int n = min(tile_carry, p.max_tiles);
+    const int per_thread = (n + kThreads - 1) / kThreads;
+    const int i0 = min(n, tid * per_thread), i1 = min(n, i0 + per_thread);
+    auto size_class = [](int rows) { return min(kSizeBins - 1, (rows + 31) >> 5); };
+    int mine[kSizeBins];
+#pragma unroll
+    for (int b = 0; b < kSizeBins; ++b) mine[b] = 0;
+    for (int i = i0; i < i1; ++i) {
+        const int c = size_class(staged[i].rows);
+#pragma unroll
+        for (int b = 0; b < kSizeBins; ++b) mine[b] += (b == c);
+    }
+    // two classes per scan (16-bit fields: a field's total is at most kSortMax)
+    int carry = 0;
+#pragma unroll
+    for (int b = kSizeBins - 1; b >= 1; b -= 2) {
+        int tot;
+        const int ex = block_exclusive_scan(mine[b] | (mine[b - 1] << 16), scratch, &tot);
+        bin_cnt[b][tid] = carry + (ex & 0xffff);
+        carry += tot & 0xffff;
+        bin_cnt[b - 1][tid] = carry + (ex >> 16);
+        carry += tot >> 16;
+    }
+    for (int i = i0; i < i1; ++i) {
+        const MTile mt = staged[i];
+        const int c = size_class(mt.rows);
+        p.tiles[bin_cnt[c][tid]++] = mt;
     }
 }
 
@@ -160,13 +203,13 @@ __global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
 
 }  // namespace
 
-hipError_t launch_permute(const Pass &p, int tile_rows, hipStream_t st)
+hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStream_t st)
 {
     const int n_assign = p.T * p.kk;
     const int nb = (n_assign + kAssignPerBlock - 1) / kAssignPerBlock;   // histogram blocks
     const int nbp = (n_assign + kThreads - 1) / kThreads;                 // placement blocks
     hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * p.S, st, p);
-    hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows);
+    hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows, sort_tiles ? 1 : 0);
     hipLaunchKernelGGL(k_slot_place, dim3(nbp), dim3(kThreads), 0, st, p);
     return hipGetLastError();
 }

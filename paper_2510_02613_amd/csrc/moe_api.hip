@@ -390,7 +390,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     mark(MOE_PHASE_GATE);
     if (e == hipSuccess && !routed_ids) e = launch_gate(p, st);
     mark(MOE_PHASE_PERMUTE);
-    if (e == hipSuccess) e = launch_permute(p, tile_rows, st);
+    if (e == hipSuccess) e = launch_permute(p, tile_rows, big, st);   // the large-tile kernels deal a size-ordered list round-robin to the XCDs
     mark(MOE_PHASE_GEMM1);
     if (e == hipSuccess) {
         if (identity)  e = launch_identity_experts(p, st);
