@@ -111,6 +111,8 @@ typedef struct {
     const void    *h;         /* [A,I]    act_dtype, silu(gate)*up */
     const void    *y;         /* [A,H]    act_dtype, expert outputs before combine */
     const int32_t *active_map;/* [E + n_shared] the device copy of the active map, shared slots last */
+    const int32_t *tiles;     /* [n_tiles][4] the M-tile list of the expert kernels: slot, first grouped row, rows, 0 */
+    const int32_t *n_tiles;   /* [1] */
 } moe_workspace_view_t;
 
 /* moe_forward flags */

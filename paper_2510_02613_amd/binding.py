@@ -46,7 +46,7 @@ class MoEBuffers(ctypes.Structure):
 
 class MoEWorkspaceView(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("topk_ids", "topk_w", "counts", "offsets", "perm", "inv", "h", "y", "active_map")]
+                ("topk_ids", "topk_w", "counts", "offsets", "perm", "inv", "h", "y", "active_map", "tiles", "n_tiles")]
 
 
 class MoEError(RuntimeError):

@@ -325,6 +325,8 @@ moe_status_t moe_workspace_view(const moe_layer_t *l, moe_workspace_view_t *v)
     v->h = ws + l->lay.h;
     v->y = ws + l->lay.y;
     v->active_map = (const int32_t *)(ws + l->lay.map[l->active]);
+    v->tiles = (const int32_t *)(ws + l->lay.tiles);
+    v->n_tiles = (const int32_t *)(ws + l->lay.n_tiles);
     return MOE_OK;
 }
 

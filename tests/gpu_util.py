@@ -151,6 +151,17 @@ def check_bookkeeping(case: Case, v: dict, T: int, shared_range):
     for s in range(S):
         r = inv[slot == s]
         assert (np.diff(r) > 0).all()
+    # the M-tile list of the expert kernels: every grouped row in exactly one tile of its own slot
+    tiles = v["tiles"]
+    if A:
+        assert (tiles[:, 2] > 0).all() and (tiles[:, 3] == 0).all()
+        covered = np.zeros(A, np.int32)
+        for s_, r0, n, _ in tiles:
+            assert offs[s_] <= r0 and r0 + n <= offs[s_ + 1], "a tile leaves its slot's rows"
+            covered[r0:r0 + n] += 1
+        assert (covered == 1).all(), "tiles do not partition the grouped rows"
+    else:
+        assert len(tiles) == 0
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:

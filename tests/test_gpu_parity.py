@@ -252,3 +252,21 @@ def test_tiled_gate_kernel_grouped_sigmoid():
                      gate="sigmoid_group", n_group=8, topk_group=3, routed_scale=2.5, n_shared=1,
                      shared_range=(0, 700), seed=17)
     _full_check(_case(wl), flags=MOE_FLAG_GATE_TILED)
+
+
+def test_large_tile_list_is_ordered_by_size():
+    """Where the large-tile kernels run, chunks hold at most 320 rows and the list is ordered by their
+    number of 32-row token tiles, largest first, slots in order within a size (the order the kernels
+    deal to the XCDs); Zipf-skewed routing gives chunks of every size."""
+    wl = MoEWorkload(name="big8z", tokens=4000, **{**SMALL, "inter": 128, "hidden": 320, "n_experts": 32, "n_slots": 32,
+                                                   "n_local": 32, "zipf_s": 1.2, "seed": 18})
+    case = _case(wl)
+    _, v, _ = _full_check(case)
+    tiles = v["tiles"]
+    assert tiles[:, 2].max() <= 320 and len(tiles) > 40
+    cls = (tiles[:, 2] + 31) // 32
+    assert (np.diff(cls) <= 0).all()
+    for c in np.unique(cls):
+        same = tiles[cls == c]
+        assert (np.diff(same[:, 0] * (1 << 20) + same[:, 1]) > 0).all()    # stable: slot order, then row order
+    assert len(np.unique(cls)) >= 4
