@@ -579,6 +579,7 @@ hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
     // being the critical path.  Measured crossover: about 128 MB of router re-reads.
     const size_t router_rereads = (size_t)((p.T + 15) / 16) * p.E * p.H * (p.router_bf16 ? 2 : 4);
     if (!p.gate_tiled && (p.T <= 256 || router_rereads <= (size_t)128 << 20)) e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
+    else if (gate_dma_supports(p))      e = launch_gate_logits_dma(p, st);             // LDS ring filled by direct copies
     else if (p.E > 64 && p.T >= 8192)   e = launch_gate_logits_lds<WT, 4, 2>(p, st);   // 64 tokens x 128 experts
     else                                e = launch_gate_logits_lds<WT, 2, 1>(p, st);   // 32 tokens x 64 experts
     if (e != hipSuccess) return e;

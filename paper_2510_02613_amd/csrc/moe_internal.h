@@ -57,6 +57,8 @@ constexpr int kAssignPerBlock = 1024;  // assignments ranked by one block of the
 hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, int blocks, hipStream_t st);  // bytes % 16 == 0
 hipError_t launch_gate(const Pass &p, hipStream_t st);
+hipError_t launch_gate_logits_dma(const Pass &p, hipStream_t st);   // logits only, bf16 activations
+bool gate_dma_supports(const Pass &p);
 hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStream_t st);
 // which: 0 = first GEMM (gather + SwiGLU), 1 = second GEMM
 hipError_t launch_experts_generic(const Pass &p, int which, hipStream_t st);

@@ -245,6 +245,14 @@ def test_tiled_gate_kernel_small_shapes(tokens, router):
     _full_check(_case(wl), flags=MOE_FLAG_GATE_TILED)
 
 
+def test_tiled_gate_kernel_ragged_contraction():
+    """H = 264 is not a whole number of 64-wide K-steps: the tiled gate then stages through registers
+    (zero-filled tail) instead of direct copies."""
+    from paper_2510_02613_amd.binding import MOE_FLAG_GATE_TILED
+    wl = MoEWorkload(name="tiled_gate_r", tokens=500, **{**SMALL, "hidden": 264, "seed": 19})
+    _full_check(_case(wl), flags=MOE_FLAG_GATE_TILED)
+
+
 def test_tiled_gate_kernel_grouped_sigmoid():
     from paper_2510_02613_amd.binding import MOE_FLAG_GATE_TILED
     wl = MoEWorkload(name="tiled_gate_g", tokens=700, hidden=256, inter=136, n_experts=160, top_k=4,
