@@ -107,12 +107,15 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
     // 1. per slot: running sum over blocks (blk_hist becomes the block's exclusive base)
     for (int s = tid; s < S; s += kThreads) {
         int run = 0;
-#pragma unroll 4
-        for (int b = 0; b < n_blocks; ++b) {
-            int32_t *q = p.blk_hist + (size_t)b * S + s;
-            int c = *q;
-            *q = run;
-            run += c;
+        for (int b0 = 0; b0 < n_blocks; b0 += 16) {   // 16 loads in flight, then their running sum
+            int c[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] = b0 + i < n_blocks ? p.blk_hist[(size_t)(b0 + i) * S + s] : 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (b0 + i < n_blocks) p.blk_hist[(size_t)(b0 + i) * S + s] = run;
+                run += c[i];
+            }
         }
         p.counts[s] = run;
     }
