@@ -26,25 +26,27 @@ namespace {
 constexpr int kThreads = 256;               // scan and place kernels
 constexpr int kHistThreads = kAssignPerBlock;  // one thread per assignment, 16 wavefronts
 
-__global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
+// slot of assignment a (token a / kk, column a % kk), or -1 when it is not this rank's
+__device__ __forceinline__ int slot_of(const Pass &p, int a)
 {
-    extern __shared__ int32_t hist[];   // [S] rows per slot seen so far in this block
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int s = tid; s < p.S; s += kHistThreads) hist[s] = 0;
-    const int a = blockIdx.x * kHistThreads + tid;
-    const int n_assign = p.T * p.kk;
-    int slot = -1;
-    if (a < n_assign) {
-        const int t = a / p.kk, j = a - t * p.kk;
-        if (j < p.k) {
-            // ids come from the gate, or from the caller when the routing is given: an id outside
-            // [0, E) is an assignment that does not exist
-            const int id = p.ids[(size_t)t * p.k + j];
-            slot = (unsigned)id < (unsigned)p.E ? p.map[id] : -1;
-        } else if (t >= p.shared_begin && t < p.shared_end) {
-            slot = p.map[p.E + (j - p.k)];
-        }
+    if (a >= p.T * p.kk) return -1;
+    const int t = a / p.kk, j = a - t * p.kk;
+    if (j < p.k) {
+        // ids come from the gate, or from the caller when the routing is given: an id outside
+        // [0, E) is an assignment that does not exist
+        const int id = p.ids[(size_t)t * p.k + j];
+        return (unsigned)id < (unsigned)p.E ? p.map[id] : -1;
     }
+    if (t >= p.shared_begin && t < p.shared_end) return p.map[p.E + (j - p.k)];
+    return -1;
+}
+
+// Rank of this thread's assignment among the earlier assignments of the block with the same slot
+// (thread order), and the block's rows per slot in hist[S] (LDS, zeroed here).
+__device__ __forceinline__ int rank_in_block(int slot, int32_t *hist, int S)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int s = tid; s < S; s += kHistThreads) hist[s] = 0;
     // rank among the earlier lanes of this wavefront with the same slot
     int rank = 0;
     for (int i = 0; i < 63; ++i) {
@@ -61,12 +63,23 @@ __global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
         if (wave == w && slot >= 0) atomicAdd(&hist[slot], 1);
         __syncthreads();
     }
-    if (a < n_assign) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
+    return rank;
+}
+
+__global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
+{
+    extern __shared__ int32_t hist[];   // [S] rows per slot seen so far in this block
+    const int tid = threadIdx.x;
+    const int a = blockIdx.x * kHistThreads + tid;
+    const int slot = slot_of(p, a);
+    const int rank = rank_in_block(slot, hist, p.S);
+    if (a < p.T * p.kk) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
     for (int s = tid; s < p.S; s += kHistThreads) p.blk_hist[(size_t)blockIdx.x * p.S + s] = hist[s];
 }
 
-// exclusive scan of v over the 256 threads of the block (v is per-thread), returns the
-// exclusive prefix; *total receives the block sum.  scratch: 8 ints of LDS.
+// exclusive scan of v over the NT threads of the block (v is per-thread), returns the
+// exclusive prefix; *total receives the block sum.  scratch: NT/64 ints of LDS.
+template <int NT = kThreads>
 __device__ __forceinline__ int block_exclusive_scan(int v, int32_t *scratch, int *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -80,7 +93,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int32_t *scratch, int
     __syncthreads();
     int base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < kThreads / 64; ++w) {
+    for (int w = 0; w < NT / 64; ++w) {
         int s = scratch[w];
         if (w < wave) base += s;
         tot += s;
@@ -88,6 +101,25 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int32_t *scratch, int
     __syncthreads();
     *total = tot;
     return base + incl - v;
+}
+
+// The M-tiles of one slot: its c rows split into nt nearly equal chunks (multiples of 32 rows, or of
+// tile_rows when that is smaller) so that no chunk is a sliver.
+__device__ __forceinline__ void emit_tiles(const Pass &p, int s, int c, int nt, int row_off, int tile_off, int tile_rows, MTile *dst)
+{
+    const int gran = tile_rows < 32 ? tile_rows : 32;
+    const int per = nt ? min(tile_rows, ((c + nt - 1) / nt + gran - 1) / gran * gran) : 0;
+    for (int i = 0; i < nt; ++i) {
+        const int idx = tile_off + i;
+        if (idx < p.max_tiles) {
+            MTile mt;
+            mt.slot = s;
+            mt.row_begin = row_off + i * per;
+            mt.rows = max(0, min(per, c - i * per));
+            mt.pad = 0;
+            dst[idx] = mt;
+        }
+    }
 }
 
 constexpr int kSortMax = 2048;   // tile lists up to this long can be ordered by size (staged in LDS)
@@ -131,22 +163,7 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
         const int tile_off = tile_carry + block_exclusive_scan(nt, scratch, &tile_tot);
         if (s < S) {
             p.offs[s] = row_off;
-            // split the slot's rows into nt nearly equal chunks (multiples of 32 rows, or of
-            // tile_rows when that is smaller) so that no chunk is a sliver
-            const int gran = tile_rows < 32 ? tile_rows : 32;
-            const int per = nt ? min(tile_rows, ((c + nt - 1) / nt + gran - 1) / gran * gran) : 0;
-            for (int i = 0; i < nt; ++i) {
-                const int idx = tile_off + i;
-                if (idx < p.max_tiles) {
-                    MTile mt;
-                    mt.slot = s;
-                    mt.row_begin = row_off + i * per;
-                    mt.rows = max(0, min(per, c - i * per));
-                    mt.pad = 0;
-                    if (staging) staged[idx] = mt;
-                    else         p.tiles[idx] = mt;
-                }
-            }
+            emit_tiles(p, s, c, nt, row_off, tile_off, tile_rows, staging ? staged : p.tiles);
         }
         row_carry += row_tot;
         tile_carry += tile_tot;
@@ -204,6 +221,49 @@ __global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
     p.inv[a] = row;
 }
 
+// The three steps in one workgroup, for passes with at most kAssignPerBlock assignments (decode-sized
+// batches, where three launches cost more than the work): slot and in-block rank of every
+// assignment, scan over the slots (offsets and tile list, kept in LDS for the placement), placement.
+__global__ __launch_bounds__(kHistThreads) void k_permute_one_block(Pass p, int tile_rows)
+{
+    extern __shared__ int32_t sm[];     // hist[S] then offs[S]
+    __shared__ int32_t scratch[kHistThreads / 64];
+    const int S = p.S, tid = threadIdx.x;
+    int32_t *hist = sm, *offs = sm + S;
+    const int slot = slot_of(p, tid);
+    const int rank = rank_in_block(slot, hist, S);
+    int row_carry = 0, tile_carry = 0;
+    for (int s0 = 0; s0 < S; s0 += kHistThreads) {
+        const int s = s0 + tid;
+        const int c = s < S ? hist[s] : 0;
+        const int nt = (c + tile_rows - 1) / tile_rows;
+        int row_tot, tile_tot;
+        const int row_off = row_carry + block_exclusive_scan<kHistThreads>(c, scratch, &row_tot);
+        const int tile_off = tile_carry + block_exclusive_scan<kHistThreads>(nt, scratch, &tile_tot);
+        if (s < S) {
+            p.counts[s] = c;
+            p.offs[s] = row_off;
+            offs[s] = row_off;
+            emit_tiles(p, s, c, nt, row_off, tile_off, tile_rows, p.tiles);
+        }
+        row_carry += row_tot;
+        tile_carry += tile_tot;
+    }
+    if (tid == 0) {
+        p.offs[S] = row_carry;
+        *p.n_tiles = min(tile_carry, p.max_tiles);
+    }
+    __syncthreads();
+    if (tid < p.T * p.kk) {
+        int row = -1;
+        if (slot >= 0) {
+            row = offs[slot] + rank;
+            p.perm[row] = tid / p.kk;
+        }
+        p.inv[tid] = row;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStream_t st)
@@ -211,6 +271,10 @@ hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStre
     const int n_assign = p.T * p.kk;
     const int nb = (n_assign + kAssignPerBlock - 1) / kAssignPerBlock;   // histogram blocks
     const int nbp = (n_assign + kThreads - 1) / kThreads;                 // placement blocks
+    if (nb == 1 && !sort_tiles && 2 * sizeof(int32_t) * p.S <= 48 * 1024) {
+        hipLaunchKernelGGL(k_permute_one_block, dim3(1), dim3(kHistThreads), 2 * sizeof(int32_t) * p.S, st, p, tile_rows);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * p.S, st, p);
     hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows, sort_tiles ? 1 : 0);
     hipLaunchKernelGGL(k_slot_place, dim3(nbp), dim3(kThreads), 0, st, p);
