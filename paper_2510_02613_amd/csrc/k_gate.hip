@@ -139,17 +139,35 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
     // top-k by repeated wavefront arg-max
     int my_id = 0;
     float my_s = 0.f;
-    for (int j = 0; j < p.k; ++j) {
-        unsigned long long key = 0ull;
-        for (int e = lane; e < E; e += 64) {
-            float v = cs[e];
-            if (v != NEG) { unsigned long long kk = make_key(v, e); key = kk > key ? kk : key; }
+    constexpr int kRegs = 8;   // up to 512 experts: the candidates live in registers, entry i of a lane is expert lane + 64 i
+    if (E <= 64 * kRegs) {
+        float c[kRegs];
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i) c[i] = lane + 64 * i < E ? cs[lane + 64 * i] : NEG;
+        for (int j = 0; j < p.k; ++j) {
+            unsigned long long key = 0ull;
+#pragma unroll
+            for (int i = 0; i < kRegs; ++i)
+                if (c[i] != NEG) { const unsigned long long kk = make_key(c[i], lane + 64 * i); key = kk > key ? kk : key; }
+            const int win = key_index(wave_max_u64(key));
+            if (lane == j) { my_id = win; my_s = lg[win]; }
+#pragma unroll
+            for (int i = 0; i < kRegs; ++i)
+                if (lane + 64 * i == win) c[i] = NEG;
         }
-        key = wave_max_u64(key);
-        int win = key_index(key);
-        if (lane == j) { my_id = win; my_s = lg[win]; }
-        if (lane == (win & 63)) cs[win] = NEG;
-        wave_sync();
+    } else {
+        for (int j = 0; j < p.k; ++j) {
+            unsigned long long key = 0ull;
+            for (int e = lane; e < E; e += 64) {
+                float v = cs[e];
+                if (v != NEG) { unsigned long long kk = make_key(v, e); key = kk > key ? kk : key; }
+            }
+            key = wave_max_u64(key);
+            int win = key_index(key);
+            if (lane == j) { my_id = win; my_s = lg[win]; }
+            if (lane == (win & 63)) cs[win] = NEG;
+            wave_sync();
+        }
     }
     float sum = wave_sum_f32(lane < p.k ? my_s : 0.f);
     if (lane < p.k) {

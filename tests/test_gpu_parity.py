@@ -278,3 +278,12 @@ def test_large_tile_list_is_ordered_by_size():
         same = tiles[cls == c]
         assert (np.diff(same[:, 0] * (1 << 20) + same[:, 1]) > 0).all()    # stable: slot order, then row order
     assert len(np.unique(cls)) >= 4
+
+
+@pytest.mark.parametrize("experts", [576, 1024])
+def test_many_experts_selection_paths(experts):
+    """More than 512 experts: the top-k candidates no longer fit a wavefront's registers and the
+    selection walks LDS instead; 1024 is the most the layer accepts."""
+    wl = MoEWorkload(name="many_experts", tokens=150, hidden=128, inter=64, n_experts=experts, top_k=6,
+                     n_slots=32, n_local=32, act_dtype="bf16", router_dtype="f32", gate="softmax", seed=20)
+    _full_check(_case(wl))
