@@ -298,12 +298,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     // within one unit -- and workgroup ids are dealt round-robin to the XCDs by the hardware, so
     // workgroup b works for XCD b % 8 and takes that XCD's units in order, the N-slices of a unit
     // on consecutive workgroups (they share the chunk's token rows in that XCD's L2).  A chunk is
-    // one unit when there are enough chunks to balance the XCDs (16 units each); otherwise its
-    // N-slices are split into g equal runs, g the smallest divisor that gives enough units.
+    // one unit when the chunks deal out evenly enough (at most 5 % of an XCD's share idle if they
+    // were all alike); otherwise its N-slices are split into g equal runs, g the smallest divisor
+    // that does -- every extra run of a chunk costs one more XCD a fetch of the chunk's token rows.
     const int n_chunks = *p.n_tiles;
     int g = n_ntiles;
-    for (int d = 1; d < n_ntiles; ++d)
-        if (n_ntiles % d == 0 && n_chunks * d >= 16 * kXcds) { g = d; break; }
+    for (int d = 1; d < n_ntiles; ++d) {
+        const int units = n_chunks * d, dealt = (units + kXcds - 1) / kXcds * kXcds;
+        if (n_ntiles % d == 0 && (dealt - units) * 20 <= units) { g = d; break; }
+    }
     const int spp = n_ntiles / g;                      // N-slices per unit
     const int b = blockIdx.x;
     const int j = b / kXcds;
