@@ -7,9 +7,9 @@
 // tile list, built from the active expert map (Sec. 3.2 / 4.6: placement is data,
 // not layout), only names slots that have rows.
 //
-// One wavefront owns 32 weight rows of one M-tile (<= 16 grouped rows) and walks
-// the whole contraction: GEMM-1 takes 16 gate rows and the 16 matching up rows (so
-// silu(g)*u is formed in registers), GEMM-2 takes 32 consecutive W2 rows.  Weights
+// One wavefront owns a block of weight rows of one M-tile (<= 16 grouped rows) and
+// walks the whole contraction: GEMM-1 takes 16 gate rows and the 16 matching up rows
+// (so silu(g)*u is formed in registers), GEMM-2 takes 16 consecutive W2 rows.  Weights
 // and token rows go straight from global memory into MFMA operand layout, as in
 // the gate kernel: for a K-chunk of 128, lane (n = l%16, q = l/16) reads the 32 k
 // {jj*32 + q*8 + i} of row n with four 16-byte loads issued back to back, so every
@@ -42,12 +42,16 @@ __device__ __forceinline__ void load_run(Run &r, const uint16_t *row, int k0, in
     }
 }
 
+constexpr int kBlocks2 = 1;   // 16-row weight blocks per wavefront in GEMM-2: its contraction is short (I), and
+                              // twice as many, half as long tasks keep more of the chip streaming to the end
+
 template <bool kFirst>
 __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
 {
     const int K = kFirst ? p.H : p.I;
     const int N = kFirst ? p.I : p.H;                       // output columns
-    constexpr int COLS = kFirst ? kWRows / 2 : kWRows;      // output columns per wavefront
+    constexpr bool kTwo = kFirst || kBlocks2 == 2;          // two weight rows per lane
+    constexpr int COLS = kFirst ? kWRows / 2 : 16 * kBlocks2;   // output columns per wavefront
     const int groups = (N + COLS - 1) / COLS;               // wavefront tasks per M-tile
     const int lane = threadIdx.x;
     const int task = blockIdx.x;
@@ -69,19 +73,19 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
     f32x4 acc_a = {0.f, 0.f, 0.f, 0.f}, acc_b = {0.f, 0.f, 0.f, 0.f};
     Run ca, cb, cx, na, nb, nx;
     load_run(ca, wa, 0, q, K);
-    load_run(cb, wb, 0, q, K);
+    if (kTwo) load_run(cb, wb, 0, q, K);
     load_run(cx, xr, 0, q, K);
     for (int k0 = 0; k0 < K; k0 += 128) {
         if (k0 + 128 < K) {
             load_run(na, wa, k0 + 128, q, K);
-            load_run(nb, wb, k0 + 128, q, K);
+            if (kTwo) load_run(nb, wb, k0 + 128, q, K);
             load_run(nx, xr, k0 + 128, q, K);
         }
         __builtin_amdgcn_sched_barrier(0);  // the prefetch must be issued before this chunk's MFMAs, not after
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             acc_a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&ca.v[jj], *(bf16x8 *)&cx.v[jj], acc_a, 0, 0, 0);
-            acc_b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&cb.v[jj], *(bf16x8 *)&cx.v[jj], acc_b, 0, 0, 0);
+            if (kTwo) acc_b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&cb.v[jj], *(bf16x8 *)&cx.v[jj], acc_b, 0, 0, 0);
         }
         ca = na; cb = nb; cx = nx;
     }
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
     } else {
         const int c0 = n0 + 4 * q, c1 = n0 + 16 + 4 * q;
         if (c0 < N) *(uint2 *)(O + c0) = pack(acc_a[0], acc_a[1], acc_a[2], acc_a[3]);
-        if (c1 < N) *(uint2 *)(O + c1) = pack(acc_b[0], acc_b[1], acc_b[2], acc_b[3]);
+        if (kTwo && c1 < N) *(uint2 *)(O + c1) = pack(acc_b[0], acc_b[1], acc_b[2], acc_b[3]);
     }
 }
 
@@ -119,7 +123,7 @@ hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st)
         const int blocks = p.max_tiles * groups;
         hipLaunchKernelGGL((k_expert_decode<true>), dim3(blocks), dim3(kThreads), 0, st, p);
     } else {
-        const int groups = (p.H + kWRows - 1) / kWRows;
+        const int groups = (p.H + 16 * kBlocks2 - 1) / (16 * kBlocks2);
         const int blocks = p.max_tiles * groups;
         hipLaunchKernelGGL((k_expert_decode<false>), dim3(blocks), dim3(kThreads), 0, st, p);
     }
