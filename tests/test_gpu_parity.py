@@ -287,3 +287,11 @@ def test_many_experts_selection_paths(experts):
     wl = MoEWorkload(name="many_experts", tokens=150, hidden=128, inter=64, n_experts=experts, top_k=6,
                      n_slots=32, n_local=32, act_dtype="bf16", router_dtype="f32", gate="softmax", seed=20)
     _full_check(_case(wl))
+
+
+def test_configuration_limits():
+    """The largest gate the layer accepts: 1024 experts in 64 groups, 32 selected per token, 4 shared experts."""
+    wl = MoEWorkload(name="limits", tokens=90, hidden=128, inter=64, n_experts=1024, top_k=32,
+                     n_slots=68, n_local=64, act_dtype="bf16", router_dtype="bf16", gate="sigmoid_group",
+                     n_group=64, topk_group=40, routed_scale=1.5, n_shared=4, shared_range=(5, 77), seed=23)
+    _full_check(_case(wl))
