@@ -11,6 +11,8 @@
 // each token to one 64-lane wavefront: scores live in LDS, every arg-max is a
 // wavefront reduction over a 64-bit (score, inverted index) key, so ties go to
 // the lower index exactly as the ordering rule demands.
+#include <type_traits>
+
 #include "moe_internal.h"
 
 namespace emoe {
@@ -141,20 +143,28 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
     float my_s = 0.f;
     constexpr int kRegs = 8;   // up to 512 experts: the candidates live in registers, entry i of a lane is expert lane + 64 i
     if (E <= 64 * kRegs) {
-        float c[kRegs];
+        // NR = registers in use; the winners' scores are fetched once, after the last round
+        auto rounds = [&](auto nr) {
+            constexpr int NR = decltype(nr)::value;
+            float c[NR];
 #pragma unroll
-        for (int i = 0; i < kRegs; ++i) c[i] = lane + 64 * i < E ? cs[lane + 64 * i] : NEG;
-        for (int j = 0; j < p.k; ++j) {
-            unsigned long long key = 0ull;
+            for (int i = 0; i < NR; ++i) c[i] = lane + 64 * i < E ? cs[lane + 64 * i] : NEG;
+            for (int j = 0; j < p.k; ++j) {
+                unsigned long long key = 0ull;
 #pragma unroll
-            for (int i = 0; i < kRegs; ++i)
-                if (c[i] != NEG) { const unsigned long long kk = make_key(c[i], lane + 64 * i); key = kk > key ? kk : key; }
-            const int win = key_index(wave_max_u64(key));
-            if (lane == j) { my_id = win; my_s = lg[win]; }
+                for (int i = 0; i < NR; ++i)
+                    if (c[i] != NEG) { const unsigned long long kk = make_key(c[i], lane + 64 * i); key = kk > key ? kk : key; }
+                const int win = key_index(wave_max_u64(key));
+                if (lane == j) my_id = win;
 #pragma unroll
-            for (int i = 0; i < kRegs; ++i)
-                if (lane + 64 * i == win) c[i] = NEG;
-        }
+                for (int i = 0; i < NR; ++i)
+                    if (lane + 64 * i == win) c[i] = NEG;
+            }
+        };
+        if (E <= 128)      rounds(std::integral_constant<int, 2>{});
+        else if (E <= 256) rounds(std::integral_constant<int, 4>{});
+        else               rounds(std::integral_constant<int, kRegs>{});
+        if (lane < p.k) my_s = lg[my_id];
     } else {
         for (int j = 0; j < p.k; ++j) {
             unsigned long long key = 0ull;
