@@ -53,6 +53,7 @@ def _load():
         _lib.oracle_route.restype = None
         _lib.oracle_forward.restype = None
         _lib.oracle_forward_routed.restype = None
+        _lib.oracle_forward_replicated.restype = None
         _lib.oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -186,4 +187,38 @@ def forward_routed(spec: LayerSpec, x, w13, w2, expert_map, ids, wts, *, shared_
                                   ctypes.c_int32(int(shared_range[1])), _ptr(tok),
                                   ctypes.c_int32(int(tok.size)), _ptr(ids), _ptr(wts),
                                   ctypes.c_int32(int(identity_experts)), _ptr(out))
+    return out
+
+
+def forward_replicated(spec: LayerSpec, x, router_w, w13, w2, replicas, *, logit_bias=None,
+                       select_bias=None, shared_slots: Sequence[int] = (), shared_range=(0, 0),
+                       tokens=None, forced_ids=None, identity_experts=False) -> np.ndarray:
+    """Layer output rows (fp64) under a replicated placement: replicas[e] is the list of slots
+    that hold a copy of logical expert e (empty: the expert is on another rank); token t uses
+    copy t mod len(replicas[e])."""
+    x, router_w, w13, w2 = _c(x), _c(router_w), _c(w13), _c(w2)
+    logit_bias, select_bias = _c(logit_bias, np.float32), _c(select_bias, np.float32)
+    cfg = _cfg(spec, x, router_w, w13)
+    assert w13.shape == (spec.S, 2 * spec.I, spec.H), w13.shape
+    assert w2.shape == (spec.S, spec.H, spec.I), w2.shape
+    assert len(replicas) == spec.E
+    rep_off = np.zeros(spec.E + 1, dtype=np.int32)
+    rep_off[1:] = np.cumsum([len(r) for r in replicas])
+    rep_slots = _c(np.asarray([s for r in replicas for s in r], dtype=np.int32))
+    assert rep_slots.size == 0 or (rep_slots.min() >= 0 and rep_slots.max() < spec.S)
+    shared = _c(np.asarray(list(shared_slots), dtype=np.int32))
+    assert shared.shape == (spec.n_shared,)
+    tok = np.arange(spec.T, dtype=np.int32) if tokens is None else _c(tokens, np.int32)
+    assert tok.size == 0 or (tok.min() >= 0 and tok.max() < spec.T)
+    forced = _c(forced_ids, np.int32)
+    if forced is not None:
+        assert forced.shape == (spec.T, spec.k)
+        assert forced.min() >= 0 and forced.max() < spec.E
+    out = np.empty((tok.size, spec.H), dtype=np.float64)
+    _load().oracle_forward_replicated(ctypes.byref(cfg), _ptr(x), _ptr(router_w), _ptr(logit_bias),
+                                      _ptr(select_bias), _ptr(w13), _ptr(w2), _ptr(rep_off), _ptr(rep_slots),
+                                      _ptr(shared), ctypes.c_int32(int(shared_range[0])),
+                                      ctypes.c_int32(int(shared_range[1])), _ptr(tok),
+                                      ctypes.c_int32(int(tok.size)), _ptr(forced),
+                                      ctypes.c_int32(int(identity_experts)), _ptr(out))
     return out

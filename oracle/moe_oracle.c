@@ -34,6 +34,8 @@
  *   7. combine  out[t] = sum_j w_j y_j  + for every shared slot, if
  *               shared_begin <= t < shared_end, 1.0 * FFN_shared(x_t).
  *               A token with no contribution gets an all-zero row.
+ *      (oracle_forward_replicated: a placement may hold several copies of an
+ *               expert; token t then uses copy t mod R -- see that function.)
  *   8. tie flags (fp32 selection scores): bit 0 set when the k-th and the best
  *               unselected eligible score differ by < 1e-5; bit 1 set when the
  *               topk_group-th and next group score differ by < 1e-5.
@@ -314,6 +316,54 @@ void oracle_forward_routed(const oracle_cfg *cfg, const void *x, const void *w13
                     expert_token(cfg, x, w13, w2, t, shared_slots[i], 1.0, identity_experts, acc, a);
         }
         free(a);
+    }
+}
+
+/*
+ * The whole layer with a REPLICATED placement: a logical expert may be held in several
+ * slots of this rank (placements that copy heavily used experts to balance load; the paper
+ * names them among the distribution strategies in Sec. 2.1 and does not fix how a copy is
+ * chosen).  Step 5 becomes: expert e has R = rep_off[e+1] - rep_off[e] copies in slots
+ * rep_slots[rep_off[e] ..]; R = 0 means the expert is on another rank; token t uses copy
+ * t mod R.  Everything else as in oracle_forward (which is the case R <= 1 everywhere).
+ */
+void oracle_forward_replicated(const oracle_cfg *cfg, const void *x, const void *router_w,
+                               const float *logit_bias, const float *select_bias,
+                               const void *w13, const void *w2,
+                               const int32_t *rep_off, const int32_t *rep_slots,
+                               const int32_t *shared_slots, int32_t shared_begin, int32_t shared_end,
+                               const int32_t *tok, int32_t n_tok, const int32_t *forced_ids,
+                               int32_t identity_experts, double *out)
+{
+#pragma omp parallel
+    {
+        double *s = malloc(sizeof(double) * cfg->E);
+        float *c = malloc(sizeof(float) * cfg->E);
+        uint8_t *el = malloc(cfg->E);
+        float *gs = malloc(sizeof(float) * (cfg->n_group > 0 ? cfg->n_group : 1));
+        int32_t *ids = malloc(sizeof(int32_t) * cfg->k);
+        double *w = malloc(sizeof(double) * cfg->k);
+        double *a = malloc(sizeof(double) * cfg->I);
+#pragma omp for schedule(dynamic, 1)
+        for (int n = 0; n < n_tok; ++n) {
+            const int t = tok[n];
+            double *acc = out + (size_t)n * cfg->H;
+            for (int h = 0; h < cfg->H; ++h) acc[h] = 0.0;
+            route_token(cfg, x, router_w, logit_bias, select_bias, t,
+                        forced_ids ? forced_ids + (size_t)t * cfg->k : NULL,
+                        ids, w, NULL, NULL, s, c, el, gs);
+            for (int j = 0; j < cfg->k; ++j) {
+                const int e = ids[j];
+                const int R = rep_off[e + 1] - rep_off[e];    /* 5. locality, with copies */
+                if (R == 0) continue;
+                const int slot = rep_slots[rep_off[e] + t % R];
+                expert_token(cfg, x, w13, w2, t, slot, w[j], identity_experts, acc, a);
+            }
+            for (int i = 0; i < cfg->n_shared; ++i)           /* 7. shared experts */
+                if (t >= shared_begin && t < shared_end)
+                    expert_token(cfg, x, w13, w2, t, shared_slots[i], 1.0, identity_experts, acc, a);
+        }
+        free(s); free(c); free(el); free(gs); free(ids); free(w); free(a);
     }
 }
 

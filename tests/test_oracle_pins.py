@@ -441,3 +441,61 @@ def test_routed_entry_with_own_routing_equals_the_gated_layer():
     np.testing.assert_allclose(routed, full, rtol=0, atol=2e-7 * np.abs(full).max())
     sub = np.array([7, 2, 2, 10], dtype=np.int32)
     np.testing.assert_array_equal(oracle.forward_routed(spec, x, w13, w2, emap, ids, w32, tokens=sub), routed[sub])
+
+
+# --------------------------------------------- replicated placement (step 5) ----
+
+def test_replicated_placement_against_library_ffn_with_distinct_copies():
+    """Copies that hold DIFFERENT weights expose which copy a token uses: row t is
+    sum_j w_j * FFN_{replicas[e_j][t mod R]}(x_t) from library ops, experts with no copy add nothing."""
+    spec, x, wr, w13, w2 = small_layer(51, T=17, E=5, k=2, S=9)
+    replicas = [[4], [0, 7, 2], [], [8, 1], [3]]
+    g = rnd(52)
+    forced = np.stack([g.choice(spec.E, size=spec.k, replace=False) for _ in range(spec.T)]).astype(np.int32)
+    got = oracle.forward_replicated(spec, x, wr, w13, w2, replicas, forced_ids=forced)
+    # weights from the gate definition, library softmax in fp64
+    s = scipy.special.softmax(x.astype(np.float64) @ wr.astype(np.float64).T, axis=1)
+    want = np.zeros((spec.T, spec.H))
+    used = set()
+    for t in range(spec.T):
+        wsum = sum(s[t, e] for e in forced[t])
+        for e in forced[t]:
+            if replicas[e]:
+                slot = replicas[e][t % len(replicas[e])]
+                used.add(slot)
+                want[t] += s[t, e] / wsum * lib_ffn(x[t:t + 1], w13[slot], w2[slot])[0]
+    assert used == {0, 1, 2, 3, 4, 7, 8}          # every copy is exercised
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-12)
+
+
+def test_replicated_placement_with_equal_copies_is_the_unreplicated_layer():
+    """Replication must not change the function: with identical weights in all copies of an expert the
+    output equals that of the plain map, bit for bit, whatever the number of copies."""
+    spec, x, wr, w13, w2 = small_layer(53, T=23, E=6, k=3, S=12, gate="sigmoid_group", n_group=2, topk_group=1,
+                                       routed_scale=2.5, n_shared=1)
+    emap = np.array([0, 1, -1, 3, 4, 5], dtype=np.int32)
+    replicas = [[0, 6, 7], [1], [], [3, 8], [4, 9, 10, 11], [5]]
+    for e, r in enumerate(replicas):
+        for s_ in r[1:]:
+            w13[s_] = w13[r[0]]
+            w2[s_] = w2[r[0]]
+    plain = oracle.forward(spec, x, wr, w13, w2, emap, shared_slots=[2], shared_range=(4, 20))
+    rep = oracle.forward_replicated(spec, x, wr, w13, w2, replicas, shared_slots=[2], shared_range=(4, 20))
+    np.testing.assert_array_equal(rep, plain)
+    # and a placement with at most one copy everywhere IS the plain map
+    single = oracle.forward_replicated(spec, x, wr, w13, w2, [[s_] if s_ >= 0 else [] for s_ in emap],
+                                       shared_slots=[2], shared_range=(4, 20))
+    np.testing.assert_array_equal(single, plain)
+
+
+def test_replicated_placement_identity_experts_and_token_subset():
+    spec, x, wr, w13, w2 = small_layer(54, T=10, E=4, k=2, S=6, renormalize=False)
+    replicas = [[0, 1], [], [2, 3, 4], [5]]
+    ids, w, _ = oracle.route(spec, x, wr)
+    got = oracle.forward_replicated(spec, x, wr, w13, w2, replicas, identity_experts=True)
+    for t in range(spec.T):
+        coef = sum(w[t, j] for j in range(spec.k) if replicas[ids[t, j]])
+        np.testing.assert_allclose(got[t], coef * x[t].astype(np.float64), rtol=1e-13, atol=1e-13)
+    full = oracle.forward_replicated(spec, x, wr, w13, w2, replicas)
+    sub = np.array([9, 0, 4, 4], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.forward_replicated(spec, x, wr, w13, w2, replicas, tokens=sub), full[sub])
