@@ -55,6 +55,9 @@ def parse_args():
                     help="qwen3_relayout only: after the timed region also time the phase-A layer idle, then with the 32 "
                          "new experts being filled into free slots on a side stream by copy kernels of BLOCKS workgroups, "
                          "then the phase-B layer after the switch")
+    ap.add_argument("--replicate-hot", type=int, default=None, metavar="N",
+                    help="qwen3_relayout only: after the timed region also time the phase-A layer (32 experts resident, "
+                         "Zipf-skewed routing) with plain placement and with the N most loaded experts copied into spare slots")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one forward into a HIP graph and time replays of it (no per-kernel events, so no roofline)")
     ap.add_argument("--virtual-pool", action="store_true",
@@ -243,6 +246,12 @@ def main():
             sys.exit(2)
         result["scale_while_serve"] = scale_while_serve(torch, layer, wl, inp, x, out, stream, args)
 
+    if args.replicate_hot is not None:
+        if wl.name != "qwen3_relayout" or not 0 < args.replicate_hot <= wl.n_slots // 2:
+            print("bench.py: --replicate-hot N needs --workload qwen3_relayout and 0 < N <= %d" % (wl.n_slots // 2), file=sys.stderr)
+            sys.exit(2)
+        result["replicate_hot"] = replicate_hot(torch, layer, wl, x, out, stream, args.replicate_hot)
+
     if not args.no_ceilings:
         result["ceilings"] = measure_ceilings(torch, B, layer, stream)
 
@@ -300,6 +309,44 @@ def scale_while_serve(torch, layer, wl, inp, x, out, stream, args):
             "window_ms": busy * n, "window_ms_with_copies_running": overlap_ms,
             "fill_bytes": nbytes, "fill_ms": fill_ms, "fill_gbs": nbytes / (fill_ms * 1e-3) / 1e9,
             "ms_per_step_phase_b_after_switch": after}
+
+
+def replicate_hot(torch, layer, wl, x, out, stream, n_hot):
+    """Forward time of the phase-A layer (experts 0..31 in slots 0..31, the other slots spare) with the
+    plain placement and with a second copy of each of the n_hot most loaded experts in a spare slot."""
+    from workloads import relayout_maps
+    map_a, _ = relayout_maps(wl)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(n=16):
+        for _ in range(3):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        e0.record(stream)
+        for _ in range(n):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    layer.set_expert_map(map_a)
+    plain = timed()
+    counts = layer.view(x.shape[0])["counts"]
+    local = [e for e in range(wl.n_experts) if map_a[e] >= 0]
+    hot = sorted(local, key=lambda e: -int(counts[map_a[e]]))[:n_hot]
+    spare = [s for s in range(wl.n_slots) if s not in set(int(v) for v in map_a if v >= 0)]
+    replicas = [[int(map_a[e])] if map_a[e] >= 0 else [] for e in range(wl.n_experts)]
+    with torch.cuda.stream(stream):
+        for e in hot:
+            s = spare.pop()
+            layer.w13[s].copy_(layer.w13[int(map_a[e])])
+            layer.w2[s].copy_(layer.w2[int(map_a[e])])
+            replicas[e].append(s)
+    layer.set_expert_replicas(replicas, stream=stream)
+    rep = timed()
+    counts_rep = layer.view(x.shape[0])["counts"]
+    return {"copies": n_hot, "ms_per_step_plain": plain, "ms_per_step_replicated": rep,
+            "largest_group_rows_plain": int(counts.max()), "largest_group_rows_replicated": int(counts_rep.max()),
+            "slots_in_use_plain": int((counts > 0).sum()), "slots_in_use_replicated": int((counts_rep > 0).sum())}
 
 
 def measure_ceilings(torch, B, layer, stream):

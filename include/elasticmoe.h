@@ -110,7 +110,8 @@ typedef struct {
     const int32_t *inv;       /* [T,k+n_shared] grouped row of every assignment or -1 */
     const void    *h;         /* [A,I]    act_dtype, silu(gate)*up */
     const void    *y;         /* [A,H]    act_dtype, expert outputs before combine */
-    const int32_t *active_map;/* [E + n_shared] the device copy of the active map, shared slots last */
+    const int32_t *active_map;/* [E + n_shared] the device copy of the active map, shared slots last
+                               * (an entry <= -2 stands for an expert with several copies) */
     const int32_t *tiles;     /* [n_tiles][4] the M-tile list of the expert kernels: slot, first grouped row, rows, 0 */
     const int32_t *n_tiles;   /* [1] */
 } moe_workspace_view_t;
@@ -153,6 +154,29 @@ moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf,
  */
 moe_status_t moe_set_expert_map(moe_layer_t *layer, const int32_t *host_map, int32_t n,
                                 const int32_t *host_shared_slots, void *hip_stream);
+
+/*
+ * Install a placement in which an expert may be held in SEVERAL slots of this rank
+ * (placements that copy heavily used experts to balance load: the paper lists them among
+ * the expert distribution strategies in Sec. 2.1 and leaves the choice of copy open).
+ *   host_rep_offsets [n+1]  n must equal E; expert e's copies are the slots
+ *                           host_rep_slots[host_rep_offsets[e] .. host_rep_offsets[e+1]);
+ *                           no copy = the expert lives on another rank.
+ *   host_rep_slots          all copies, expert by expert (may be NULL when there are none).
+ *   host_shared_slots [n_shared]  as in moe_set_expert_map.
+ * Token t's assignment to expert e goes to copy t mod R of its R copies: a choice that
+ * needs no state, is the same on every pass, and spreads an expert's rows evenly over its
+ * copies whenever its tokens are spread over the batch.  All copies of an expert must hold
+ * the same weights for the layer to compute the same function (not checked).
+ * Rejected with MOE_ERR_MAP, leaving the old placement active: n != E, offsets that do not
+ * start at 0, decrease or exceed S, a slot outside [0, S), a slot used twice.
+ * Everything else -- the two device tables, ordering on `hip_stream`, no allocation, no
+ * weight traffic, the wait for pending slot fills -- as in moe_set_expert_map, which is
+ * the case of at most one copy per expert.
+ */
+moe_status_t moe_set_expert_replicas(moe_layer_t *layer, const int32_t *host_rep_offsets,
+                                     const int32_t *host_rep_slots, int32_t n,
+                                     const int32_t *host_shared_slots, void *hip_stream);
 
 /*
  * Fill one slot of the weight pools in the background while forwards keep running

@@ -24,7 +24,7 @@ STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_M
 EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe_forward",
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
-           "moe_load_expert", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
+           "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
            "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy")
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
@@ -75,6 +75,9 @@ def lib() -> ctypes.CDLL:
         L.moe_set_expert_map.restype = ctypes.c_int
         L.moe_set_expert_map.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
                                          ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+        L.moe_set_expert_replicas.restype = ctypes.c_int
+        L.moe_set_expert_replicas.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                                              ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
         L.moe_forward.restype = ctypes.c_int
         L.moe_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32]
@@ -155,6 +158,14 @@ def moe_set_expert_map(layer, host_map: Sequence[int], host_shared_slots: Option
     if ns == 0:
         s = None
     _check(lib().moe_set_expert_map(layer, m, n, s, ctypes.c_void_p(stream)))
+
+
+def moe_set_expert_replicas(layer, host_rep_offsets: Sequence[int], host_rep_slots: Sequence[int],
+                            host_shared_slots: Optional[Sequence[int]] = None, stream: int = 0) -> None:
+    o, no = _i32_array(host_rep_offsets)
+    r, nr = _i32_array(host_rep_slots)
+    s, ns = _i32_array(host_shared_slots)
+    _check(lib().moe_set_expert_replicas(layer, o, r if nr else None, no - 1, s if ns else None, ctypes.c_void_p(stream)))
 
 
 def moe_forward(layer, x_ptr: int, T: int, out_ptr: int, shared_begin: int = 0, shared_end: int = 0,

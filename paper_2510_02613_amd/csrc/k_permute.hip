@@ -35,7 +35,13 @@ __device__ __forceinline__ int slot_of(const Pass &p, int a)
         // ids come from the gate, or from the caller when the routing is given: an id outside
         // [0, E) is an assignment that does not exist
         const int id = p.ids[(size_t)t * p.k + j];
-        return (unsigned)id < (unsigned)p.E ? p.map[id] : -1;
+        if ((unsigned)id >= (unsigned)p.E) return -1;
+        const int m = p.map[id];
+        if (m >= -1) return m;
+        // replicated expert: -2 - m is where its copy list (count R >= 2, then R slots) starts behind
+        // the E + n_shared entries; token t uses copy t mod R
+        const int32_t *copies = p.map + p.E + p.n_shared + (-2 - m);
+        return copies[1 + t % copies[0]];
     }
     if (t >= p.shared_begin && t < p.shared_end) return p.map[p.E + (j - p.k)];
     return -1;

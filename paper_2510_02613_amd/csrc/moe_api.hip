@@ -88,8 +88,10 @@ Layout make_layout(const moe_config_t &c)
     const size_t max_tiles = (A + kMinTileRows - 1) / kMinTileRows + S;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    L.map[0] = take(4 * (c.n_experts + c.n_shared));
-    L.map[1] = take(4 * (c.n_experts + c.n_shared));
+    // a table: E + n_shared entries, then the copy lists of replicated experts (count, slots...:
+    // at most S slots in lists of at least two, so 3S/2 entries)
+    L.map[0] = take(4 * (c.n_experts + c.n_shared + 2 * S));
+    L.map[1] = take(4 * (c.n_experts + c.n_shared + 2 * S));
     L.logits = take(c.act_dtype == MOE_BF16 ? 4 * T * c.n_experts : 0);
     L.ids = take(4 * T * k);
     L.w = take(4 * T * k);
@@ -122,7 +124,7 @@ struct moe_layer {
     Layout lay;
     int active;      // which of the two device tables forwards read
     bool has_map;
-    std::vector<int32_t> host_map;  // E + n_shared, copy of the active table
+    std::vector<int32_t> slot_owner;  // per slot: entry (expert, or E + shared expert) of the active table that uses it, or -1
     // slot fills that the next map switch has to wait for (one event per fill, reused after the switch)
     std::vector<hipEvent_t> load_ev;
     int n_pending = 0;
@@ -237,6 +239,40 @@ moe_status_t moe_profile_read(moe_layer_t *l, int32_t back, float *ms)
     return MOE_OK;
 }
 
+namespace {
+
+// Validated placement -> the inactive device table, then make it the active one.
+moe_status_t install_table(moe_layer_t *l, std::vector<int32_t> &table, std::vector<int32_t> &owner, void *hip_stream)
+{
+    const int target = l->has_map ? 1 - l->active : 0;
+    int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map[target]);
+    hipError_t e = hipSuccess;
+    // slot fills enqueued by moe_load_expert: everything after this switch on hip_stream sees them complete
+    for (int i = 0; i < l->n_pending && e == hipSuccess; ++i) e = hipStreamWaitEvent((hipStream_t)hip_stream, l->load_ev[i], 0);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "waiting for slot fills failed: %s", hipGetErrorString(e));
+    l->n_pending = 0;
+    e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
+    l->active = target;
+    l->has_map = true;
+    l->slot_owner.swap(owner);
+    return MOE_OK;
+}
+
+// entry `who` (expert e, or E + shared expert) claims slot s
+moe_status_t claim_slot(const moe_config_t &c, std::vector<int32_t> &owner, int32_t s, int who)
+{
+    const bool shared = who >= c.n_experts;
+    if (s < 0 || s >= c.n_slots)
+        return fail(MOE_ERR_MAP, "%s %d -> slot %d is outside [0, %d)", shared ? "shared expert" : "expert",
+                    shared ? who - c.n_experts : who, s, c.n_slots);
+    if (owner[s] >= 0) return fail(MOE_ERR_MAP, "slot %d is claimed twice (entries %d and %d)", s, owner[s], who);
+    owner[s] = who;
+    return MOE_OK;
+}
+
+}  // namespace
+
 moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t n,
                                 const int32_t *host_shared_slots, void *hip_stream)
 {
@@ -251,28 +287,58 @@ moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t
     for (int e = 0; e < c.n_experts + c.n_shared; ++e) {
         const bool shared = e >= c.n_experts;
         const int32_t s = shared ? host_shared_slots[e - c.n_experts] : host_map[e];
-        if (s < -1 || s >= c.n_slots || (shared && s < 0))
+        if (s < -1 || (shared && s < 0))
             return fail(MOE_ERR_MAP, "%s %d -> slot %d is outside [%s, %d)", shared ? "shared expert" : "expert",
                         shared ? e - c.n_experts : e, s, shared ? "0" : "-1", c.n_slots);
         if (s >= 0) {
-            if (owner[s] >= 0) return fail(MOE_ERR_MAP, "slot %d is claimed twice (entries %d and %d)", s, owner[s], e);
-            owner[s] = e;
+            const moe_status_t st = claim_slot(c, owner, s, e);
+            if (st != MOE_OK) return st;
         }
         table[e] = s;
     }
-    const int target = l->has_map ? 1 - l->active : 0;
-    int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map[target]);
-    hipError_t e = hipSuccess;
-    // slot fills enqueued by moe_load_expert: everything after this switch on hip_stream sees them complete
-    for (int i = 0; i < l->n_pending && e == hipSuccess; ++i) e = hipStreamWaitEvent((hipStream_t)hip_stream, l->load_ev[i], 0);
-    if (e != hipSuccess) return fail(MOE_ERR_HIP, "waiting for slot fills failed: %s", hipGetErrorString(e));
-    l->n_pending = 0;
-    e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
-    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
-    l->active = target;
-    l->has_map = true;
-    l->host_map.swap(table);
-    return MOE_OK;
+    return install_table(l, table, owner, hip_stream);
+}
+
+moe_status_t moe_set_expert_replicas(moe_layer_t *l, const int32_t *host_rep_offsets, const int32_t *host_rep_slots,
+                                     int32_t n, const int32_t *host_shared_slots, void *hip_stream)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    if (!host_rep_offsets) return fail(MOE_ERR_ARG, "host_rep_offsets is NULL");
+    const moe_config_t &c = l->cfg;
+    if (n != c.n_experts) return fail(MOE_ERR_MAP, "placement has %d experts, layer has %d logical experts", n, c.n_experts);
+    if ((c.n_shared > 0) != (host_shared_slots != nullptr))
+        return fail(MOE_ERR_MAP, "host_shared_slots must be given exactly when n_shared > 0");
+    if (host_rep_offsets[0] != 0) return fail(MOE_ERR_MAP, "host_rep_offsets[0] is %d, must be 0", host_rep_offsets[0]);
+    for (int e = 0; e < n; ++e)
+        if (host_rep_offsets[e + 1] < host_rep_offsets[e] || host_rep_offsets[e + 1] > c.n_slots)
+            return fail(MOE_ERR_MAP, "host_rep_offsets must be non-decreasing and end at no more than n_slots = %d (entry %d is %d)",
+                        c.n_slots, e + 1, host_rep_offsets[e + 1]);
+    if (host_rep_offsets[n] > 0 && !host_rep_slots) return fail(MOE_ERR_ARG, "host_rep_slots is NULL");
+    std::vector<int32_t> owner(c.n_slots, -1);
+    std::vector<int32_t> table(c.n_experts + c.n_shared);
+    for (int e = 0; e < n; ++e) {
+        const int b = host_rep_offsets[e], R = host_rep_offsets[e + 1] - b;
+        for (int r = 0; r < R; ++r) {
+            const moe_status_t st = claim_slot(c, owner, host_rep_slots[b + r], e);
+            if (st != MOE_OK) return st;
+        }
+        if (R == 0) {
+            table[e] = -1;
+        } else if (R == 1) {
+            table[e] = host_rep_slots[b];
+        } else {
+            // the copy list (count, slots) goes behind the E + n_shared entries; the entry encodes where
+            table[e] = -2 - (int32_t)(table.size() - (size_t)(c.n_experts + c.n_shared));
+            table.push_back(R);
+            for (int r = 0; r < R; ++r) table.push_back(host_rep_slots[b + r]);
+        }
+    }
+    for (int i = 0; i < c.n_shared; ++i) {
+        const moe_status_t st = claim_slot(c, owner, host_shared_slots[i], c.n_experts + i);
+        if (st != MOE_OK) return st;
+        table[c.n_experts + i] = host_shared_slots[i];
+    }
+    return install_table(l, table, owner, hip_stream);
 }
 
 moe_status_t moe_load_expert(moe_layer_t *l, int32_t slot, const void *src_w13, const void *src_w2,
@@ -285,11 +351,11 @@ moe_status_t moe_load_expert(moe_layer_t *l, int32_t slot, const void *src_w13, 
     if (!aligned(src_w13, 16) || !aligned(src_w2, 16)) return fail(MOE_ERR_ARG, "src_w13 and src_w2 must be 16-byte aligned");
     if (copy_blocks < 0 || copy_blocks > 65536) return fail(MOE_ERR_ARG, "copy_blocks %d is outside [0, 65536]", copy_blocks);
     if (copy_stream == serve_stream) return fail(MOE_ERR_ARG, "copy_stream and serve_stream must differ (the fill is meant to run beside the forwards)");
-    if (l->has_map)
-        for (size_t e = 0; e < l->host_map.size(); ++e)
-            if (l->host_map[e] == slot)
-                return fail(MOE_ERR_MAP, "slot %d holds %s %d of the active map: it cannot be refilled while forwards may read it", slot,
-                            (int)e >= c.n_experts ? "shared expert" : "expert", (int)e >= c.n_experts ? (int)e - c.n_experts : (int)e);
+    if (l->has_map && l->slot_owner[slot] >= 0) {
+        const int e = l->slot_owner[slot];
+        return fail(MOE_ERR_MAP, "slot %d holds %s %d of the active map: it cannot be refilled while forwards may read it", slot,
+                    e >= c.n_experts ? "shared expert" : "expert", e >= c.n_experts ? e - c.n_experts : e);
+    }
     hipError_t e = hipSuccess;
     if (!l->serve_ev) e = hipEventCreateWithFlags(&l->serve_ev, hipEventDisableTiming);
     if (e == hipSuccess && (int)l->load_ev.size() == l->n_pending) {

@@ -148,6 +148,16 @@ class MoELayer:
         B.moe_set_expert_map(self.handle, list(expert_map),
                              None if shared_slots is None or len(shared_slots) == 0 else list(shared_slots), s.cuda_stream)
 
+    def set_expert_replicas(self, replicas: Sequence[Sequence[int]], shared_slots: Optional[Sequence[int]] = None,
+                            stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Placement with copies: replicas[e] lists the slots holding expert e (empty: on another rank)."""
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        offs = [0]
+        for r in replicas:
+            offs.append(offs[-1] + len(r))
+        B.moe_set_expert_replicas(self.handle, offs, [int(v) for r in replicas for v in r],
+                                  None if shared_slots is None or len(shared_slots) == 0 else list(shared_slots), s.cuda_stream)
+
     # -- forward -------------------------------------------------------------
     def upload(self, x: np.ndarray) -> torch.Tensor:
         return _dev(x, self.device)

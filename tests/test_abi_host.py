@@ -148,6 +148,36 @@ def test_routed_forward_and_slot_fill_argument_checks():
         B.moe_layer_destroy(h)
 
 
+def test_replicated_placement_argument_checks():
+    """A placement with copies is validated on the host before anything is uploaded."""
+    cfg = good_cfg(n_slots=12, n_shared=1)
+    h = B.moe_layer_create(cfg, fake_buffers(cfg))
+    try:
+        ok_off = [0, 1, 4, 4, 6, 7, 8, 8, 9]                # expert 1 has 3 copies, 3 has 2, 2 and 6 are remote
+        ok_slots = [0, 1, 10, 11, 2, 3, 4, 5, 6]
+        bad = [
+            (ok_off[:8], ok_slots, [9]),                    # wrong number of experts
+            ([1] + ok_off[1:], ok_slots, [9]),              # offsets do not start at 0
+            ([0, 1, 4, 3, 6, 7, 8, 8, 9], ok_slots, [9]),   # decreasing offsets
+            ([0, 1, 4, 4, 6, 7, 8, 8, 13], ok_slots + [7, 8, 9, 9], [9]),   # more copies than slots
+            (ok_off, [0, 1, 10, 12, 2, 3, 4, 5, 6], [9]),   # slot past the pool
+            (ok_off, [0, 1, 10, -1, 2, 3, 4, 5, 6], [9]),   # a copy must have a slot
+            (ok_off, [0, 1, 10, 1, 2, 3, 4, 5, 6], [9]),    # one slot for two copies of an expert
+            (ok_off, [0, 1, 10, 11, 2, 3, 0, 5, 6], [9]),   # one slot for copies of two experts
+            (ok_off, ok_slots, [11]),                       # shared slot also holds a copy
+            (ok_off, ok_slots, None),                       # shared slots missing
+        ]
+        for o, r, s_ in bad:
+            with pytest.raises(B.MoEError) as ei:
+                B.moe_set_expert_replicas(h, o, r, s_)
+            assert ei.value.status == B.MOE_ERR_MAP, (o, r, s_)
+        with pytest.raises(B.MoEError) as ei:               # nothing was installed
+            B.moe_forward(h, 0x50000, 4, 0x60000)
+        assert ei.value.status == B.MOE_ERR_MAP
+    finally:
+        B.moe_layer_destroy(h)
+
+
 def test_valid_map_without_gpu_fails_cleanly_or_installs():
     import torch
     if torch.cuda.is_available():
