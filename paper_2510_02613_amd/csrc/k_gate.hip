@@ -583,7 +583,11 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
     float *gsc = cs + E;                      // [64]
     const int t = blockIdx.x * 4 + wave;
     if (t >= p.T) return;
-    for (int e = lane; e < E; e += 64) lg[e] = p.logits[(size_t)t * E + e];
+    for (int e = lane; e < E; e += 64) {
+        float v = p.logits[(size_t)t * E + e];
+        for (int z = 1; z < p.logit_planes; ++z) v += p.logits[((size_t)z * p.T + t) * E + e];   // partial sums, in K order
+        lg[e] = v;
+    }
     wave_sync();
     select_token(p, t, lg, cs, gsc, lane);
 }
@@ -598,8 +602,10 @@ hipError_t launch_gate_logits_t(const Pass &p, hipStream_t st)
 }
 
 template <typename WT>
-hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
+hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
 {
+    Pass p = p0;
+    int planes = 1;
     // pick the split that gives the chip enough workgroups
     hipError_t e;
     // The K-split kernel re-reads the router once per 16-token block (from L2) but fills the chip at any
@@ -607,10 +613,11 @@ hipError_t launch_gate_mfma(const Pass &p, hipStream_t st)
     // being the critical path.  Measured crossover: about 128 MB of router re-reads.
     const size_t router_rereads = (size_t)((p.T + 15) / 16) * p.E * p.H * (p.router_bf16 ? 2 : 4);
     if (!p.gate_tiled && (p.T <= 256 || router_rereads <= (size_t)128 << 20)) e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
-    else if (gate_dma_supports(p))      e = launch_gate_logits_dma(p, st);             // LDS ring filled by direct copies
+    else if (gate_dma_supports(p))      e = launch_gate_logits_dma(p, &planes, st);    // LDS ring filled by direct copies
     else if (p.E > 64 && p.T >= 8192)   e = launch_gate_logits_lds<WT, 4, 2>(p, st);   // 64 tokens x 128 experts
     else                                e = launch_gate_logits_lds<WT, 2, 1>(p, st);   // 32 tokens x 64 experts
     if (e != hipSuccess) return e;
+    p.logit_planes = planes;
     const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);
     hipLaunchKernelGGL(k_gate_select, dim3((p.T + 3) / 4), dim3(kThreads), smem, st, p);
     return hipGetLastError();

@@ -92,7 +92,7 @@ Layout make_layout(const moe_config_t &c)
     // at most S slots in lists of at least two, so 3S/2 entries)
     L.map[0] = take(4 * (c.n_experts + c.n_shared + 2 * S));
     L.map[1] = take(4 * (c.n_experts + c.n_shared + 2 * S));
-    L.logits = take(c.act_dtype == MOE_BF16 ? 4 * T * c.n_experts : 0);
+    L.logits = take(c.act_dtype == MOE_BF16 ? 4 * T * c.n_experts * kGatePlanes : 0);   // partial-sum planes of the K-split logits kernels
     L.ids = take(4 * T * k);
     L.w = take(4 * T * k);
     L.slot_rank = take(4 * A);
@@ -427,6 +427,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.w13 = l->buf.w13; p.w2 = l->buf.w2;
     p.map = (const int32_t *)(ws + l->lay.map[l->active]);
     p.logits = (float *)(ws + l->lay.logits);
+    p.logit_planes = 1;
     // the kernels after the gate only read ids and w
     p.ids = routed_ids ? const_cast<int32_t *>(routed_ids) : (int32_t *)(ws + l->lay.ids);
     p.w = routed_w ? const_cast<float *>(routed_w) : (float *)(ws + l->lay.w);

@@ -35,7 +35,8 @@ struct Pass {
     const void *w13, *w2;
     // workspace
     const int32_t *map;  // [E + n_shared] active table, shared slots last
-    float *logits;       // [T,E] gate logits (bf16-activation path)
+    float *logits;       // [logit_planes][T,E] gate logits (bf16-activation path): the planes are partial sums over K ranges
+    int32_t logit_planes;
     int32_t *ids;        // [T,k]
     float *w;            // [T,k]
     int32_t *slot_rank;  // [T*kk] (slot << 12 | rank-in-block) or -1
@@ -52,12 +53,13 @@ struct Pass {
     int32_t gate_tiled;  // the LDS-tiled gate logits kernel is forced (testing aid)
 };
 
+constexpr int kGatePlanes = 8;         // partial-sum planes of the gate logits the workspace has room for
 constexpr int kAssignPerBlock = 1024;  // assignments ranked by one block of the slot histogram kernel
 
 hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, int blocks, hipStream_t st);  // bytes % 16 == 0
 hipError_t launch_gate(const Pass &p, hipStream_t st);
-hipError_t launch_gate_logits_dma(const Pass &p, hipStream_t st);   // logits only, bf16 activations
+hipError_t launch_gate_logits_dma(const Pass &p, int *planes, hipStream_t st);   // logits only, bf16 activations
 bool gate_dma_supports(const Pass &p);
 hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStream_t st);
 // which: 0 = first GEMM (gather + SwiGLU), 1 = second GEMM
