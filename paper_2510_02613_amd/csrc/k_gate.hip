@@ -68,6 +68,20 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     lo = (unsigned)__builtin_amdgcn_readlane((int)lo, 63);
     return ((unsigned long long)hi << 32) | lo;
 }
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#define STEP(CTRL, MASK) { const uint32_t o = (uint32_t)dpp_i32<CTRL, MASK>(0, (int)v); v = o > v ? o : v; }
+    EMOE_DPP_REDUCE(STEP)
+#undef STEP
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ int wave_min_i32(int v)
+{
+#define STEP(CTRL, MASK) { const int o = dpp_i32<CTRL, MASK>(0x7fffffff, v); v = o < v ? o : v; }
+    EMOE_DPP_REDUCE(STEP)
+#undef STEP
+    return __builtin_amdgcn_readlane(v, 63);
+}
 __device__ __forceinline__ float wave_max_f32(float v)
 {
     const int ninf = (int)0xff800000u;
@@ -116,23 +130,34 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
     // group limiting
     if (p.gate == MOE_GATE_SIGMOID_GROUP_TOPK && p.n_group > 1) {
         const int G = p.n_group, per = E / G;
-        float gs = NEG;
-        if (lane < G) {
-            float b1 = NEG, b2 = NEG;
-            for (int e = lane * per; e < (lane + 1) * per; ++e) {
-                float v = cs[e];
+        // L lanes share a group's experts (L a power of two, G * L <= 64): each finds the two largest
+        // of its share, then the pairs are merged across the L lanes -- a group's score is the sum of
+        // its two largest selection scores, which does not depend on the order they are found in
+        int L = 1;
+        while (2 * L * G <= 64) L *= 2;
+        const int g = lane / L, sub = lane - g * L;
+        float b1 = NEG, b2 = NEG;
+        if (g < G) {
+            for (int e = g * per + sub; e < (g + 1) * per; e += L) {
+                const float v = cs[e];
                 if (v > b1) { b2 = b1; b1 = v; } else if (v > b2) { b2 = v; }
             }
-            gs = (per > 1) ? b1 + b2 : b1;
         }
-        // pick topk_group groups; lane g remembers whether its group was kept
+        for (int d = 1; d < L; d <<= 1) {
+            const float o1 = __shfl_xor(b1, d, 64), o2 = __shfl_xor(b2, d, 64);
+            b2 = fmaxf(fminf(b1, o1), fmaxf(b2, o2));
+            b1 = fmaxf(b1, o1);
+        }
+        const float gs = (per > 1) ? b1 + b2 : b1;
+        const bool head = g < G && sub == 0;     // the lane that speaks for group g
+        // pick topk_group groups; a group's head lane remembers whether it was kept
         bool kept = false;
         for (int r = 0; r < p.topk_group; ++r) {
-            unsigned long long key = (lane < G && !kept) ? make_key(gs, lane) : 0ull;
+            unsigned long long key = (head && !kept) ? make_key(gs, g) : 0ull;
             int win = key_index(wave_max_u64(key));
-            if (lane == win) kept = true;
+            if (head && g == win) kept = true;
         }
-        if (lane < G) gsc[lane] = kept ? 1.f : 0.f;
+        if (head) gsc[g] = kept ? 1.f : 0.f;
         wave_sync();
         for (int e = lane; e < E; e += 64)
             if (gsc[e / per] == 0.f) cs[e] = NEG;
@@ -143,22 +168,38 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
     float my_s = 0.f;
     constexpr int kRegs = 8;   // up to 512 experts: the candidates live in registers, entry i of a lane is expert lane + 64 i
     if (E <= 64 * kRegs) {
-        // NR = registers in use; the winners' scores are fetched once, after the last round
+        // NR = registers in use; the winners' scores are fetched once, after the last round.
+        // Candidates are kept as order-preserving 32-bit integers (0 = taken or absent): a round is
+        // a 32-bit wavefront maximum, and only when several lanes hold that maximum (equal scores)
+        // a second reduction for the lowest expert index among them.
         auto rounds = [&](auto nr) {
             constexpr int NR = decltype(nr)::value;
-            float c[NR];
+            uint32_t c[NR];
 #pragma unroll
-            for (int i = 0; i < NR; ++i) c[i] = lane + 64 * i < E ? cs[lane + 64 * i] : NEG;
+            for (int i = 0; i < NR; ++i) {
+                const float v = lane + 64 * i < E ? cs[lane + 64 * i] : NEG;
+                c[i] = v != NEG ? orderable(v) : 0u;
+            }
             for (int j = 0; j < p.k; ++j) {
-                unsigned long long key = 0ull;
+                uint32_t best = 0u;
+                int bi = 0;
 #pragma unroll
                 for (int i = 0; i < NR; ++i)
-                    if (c[i] != NEG) { const unsigned long long kk = make_key(c[i], lane + 64 * i); key = kk > key ? kk : key; }
-                const int win = key_index(wave_max_u64(key));
+                    if (c[i] > best) { best = c[i]; bi = i; }    // strict: the lowest index among a lane's equal scores
+                const uint32_t m = wave_max_u32(best);
+                const unsigned long long holders = __ballot(best == m && m != 0u);
+                int win;
+                if (__popcll(holders) == 1) {
+                    const int src = __ffsll((long long)holders) - 1;
+                    win = src + 64 * __builtin_amdgcn_readlane(bi, src);
+                } else {
+                    win = wave_min_i32(best == m && m != 0u ? lane + 64 * bi : 0x7fffffff);
+                    if (win == 0x7fffffff) win = -1;             // no candidate left
+                }
                 if (lane == j) my_id = win;
 #pragma unroll
                 for (int i = 0; i < NR; ++i)
-                    if (lane + 64 * i == win) c[i] = NEG;
+                    if (lane + 64 * i == win) c[i] = 0u;
             }
         };
         if (E <= 128)      rounds(std::integral_constant<int, 2>{});
