@@ -47,21 +47,55 @@ __device__ __forceinline__ int slot_of(const Pass &p, int a)
     return -1;
 }
 
+constexpr int kHistWaves = kHistThreads / 64;
+constexpr int kPerWaveSlots = 512;   // up to this many slots every wavefront has its own row of counts in LDS
+
+// LDS ints rank_in_block needs for S slots: hist[S], and below kPerWaveSlots one more row per wavefront
+__host__ __device__ constexpr size_t rank_lds_ints(int S) { return (size_t)S * (S <= kPerWaveSlots ? 1 + kHistWaves : 1); }
+
 // Rank of this thread's assignment among the earlier assignments of the block with the same slot
-// (thread order), and the block's rows per slot in hist[S] (LDS, zeroed here).
+// (thread order), and the block's rows per slot in hist[S] (LDS, written here).
 __device__ __forceinline__ int rank_in_block(int slot, int32_t *hist, int S)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int s = tid; s < S; s += kHistThreads) hist[s] = 0;
-    // rank among the earlier lanes of this wavefront with the same slot
-    int rank = 0;
-    for (int i = 0; i < 63; ++i) {
-        const int si = __builtin_amdgcn_readlane(slot, i);
-        rank += (lane > i && si == slot && slot >= 0) ? 1 : 0;
+    // The lanes of this wavefront with the same slot, found bit by bit of the slot number (a ballot per
+    // bit, each lane keeping the side it is on); from that mask the rank among the earlier lanes and
+    // whether a later lane has the slot too.
+    unsigned long long peers = __ballot(slot >= 0);
+    for (int b = 0; (S - 1) >> b; ++b) {
+        const bool bit = (slot >> b) & 1;
+        const unsigned long long ones = __ballot(bit);
+        peers &= bit ? ones : ~ones;
     }
+    const int rank0 = __popcll(peers & ((1ull << lane) - 1ull));
+    int rank = slot >= 0 ? rank0 : 0;
+    const bool last = ((peers >> lane) >> 1) == 0ull;
+    if (S <= kPerWaveSlots) {
+        // every wavefront leaves its rows per slot in its own row of counts (the last lane of a slot
+        // knows the total), then the rows are turned into running sums over the wavefronts
+        int32_t *cnt = hist + S;                      // [kHistWaves][S]
+        for (int i = tid; i < kHistWaves * S; i += kHistThreads) cnt[i] = 0;
+        __syncthreads();
+        if (slot >= 0 && last) cnt[wave * S + slot] = rank + 1;
+        __syncthreads();
+        for (int s = tid; s < S; s += kHistThreads) {
+            int run = 0;
+#pragma unroll
+            for (int w = 0; w < kHistWaves; ++w) {
+                const int c = cnt[w * S + s];
+                cnt[w * S + s] = run;
+                run += c;
+            }
+            hist[s] = run;
+        }
+        __syncthreads();
+        if (slot >= 0) rank += cnt[wave * S + slot];
+        return rank;
+    }
+    for (int s = tid; s < S; s += kHistThreads) hist[s] = 0;
     __syncthreads();
     // wavefronts take turns in order: read the slot's running count, then add this wavefront's rows
-    for (int w = 0; w < kHistThreads / 64; ++w) {
+    for (int w = 0; w < kHistWaves; ++w) {
         if (wave == w && slot >= 0) {
             rank += hist[slot];
         }
@@ -232,10 +266,10 @@ __global__ __launch_bounds__(kThreads) void k_slot_place(Pass p)
 // assignment, scan over the slots (offsets and tile list, kept in LDS for the placement), placement.
 __global__ __launch_bounds__(kHistThreads) void k_permute_one_block(Pass p, int tile_rows)
 {
-    extern __shared__ int32_t sm[];     // hist[S] then offs[S]
+    extern __shared__ int32_t sm[];     // the ranking's counts (hist[S] first), then offs[S]
     __shared__ int32_t scratch[kHistThreads / 64];
     const int S = p.S, tid = threadIdx.x;
-    int32_t *hist = sm, *offs = sm + S;
+    int32_t *hist = sm, *offs = sm + rank_lds_ints(S);
     const int slot = slot_of(p, tid);
     const int rank = rank_in_block(slot, hist, S);
     int row_carry = 0, tile_carry = 0;
@@ -277,11 +311,12 @@ hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStre
     const int n_assign = p.T * p.kk;
     const int nb = (n_assign + kAssignPerBlock - 1) / kAssignPerBlock;   // histogram blocks
     const int nbp = (n_assign + kThreads - 1) / kThreads;                 // placement blocks
-    if (nb == 1 && !sort_tiles && 2 * sizeof(int32_t) * p.S <= 48 * 1024) {
-        hipLaunchKernelGGL(k_permute_one_block, dim3(1), dim3(kHistThreads), 2 * sizeof(int32_t) * p.S, st, p, tile_rows);
+    const size_t one_block_lds = sizeof(int32_t) * (rank_lds_ints(p.S) + p.S);
+    if (nb == 1 && !sort_tiles && one_block_lds <= 48 * 1024) {
+        hipLaunchKernelGGL(k_permute_one_block, dim3(1), dim3(kHistThreads), one_block_lds, st, p, tile_rows);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * p.S, st, p);
+    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * rank_lds_ints(p.S), st, p);
     hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows, sort_tiles ? 1 : 0);
     hipLaunchKernelGGL(k_slot_place, dim3(nbp), dim3(kThreads), 0, st, p);
     return hipGetLastError();
