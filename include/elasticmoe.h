@@ -245,8 +245,10 @@ moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *
 /*
  * Phase timing for benchmarks (not part of the method; it exists so that a
  * benchmark can time each kernel of a pass on the very stream the pass runs on).
- * While enabled, every moe_forward records HIP events around its phases; the last
- * 64 forwards are kept.  moe_profile_read waits for the forward `back` passes ago
+ * While enabled, every enable-th moe_forward (enable = 1: every one; a larger value
+ * samples, so that the events' own cost -- a microsecond or two each -- stays out of
+ * most passes) records HIP events around its phases; the last 64 recorded forwards are
+ * kept.  moe_profile_read waits for the recorded forward `back` recordings ago
  * (0 = most recent) and writes the milliseconds of each phase to ms[MOE_N_PHASES].
  * Enabling creates the events (host objects), disabling or destroying the layer
  * destroys them.

@@ -228,8 +228,9 @@ def moe_workspace_view(layer) -> MoEWorkspaceView:
     return v
 
 
-def moe_profile_enable(layer, enable: bool) -> None:
-    _check(lib().moe_profile_enable(layer, int(bool(enable))))
+def moe_profile_enable(layer, enable: int) -> None:
+    """0 = off, n > 0 = record the phase events of every n-th forward."""
+    _check(lib().moe_profile_enable(layer, int(enable)))
 
 
 def moe_profile_read(layer, back: int = 0):

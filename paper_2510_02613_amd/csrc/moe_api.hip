@@ -118,6 +118,8 @@ constexpr int kProfRing = 64;  // forwards whose phase events are kept
 struct moe_layer {
     bool prof_on = false;
     long long prof_count = 0;  // forwards recorded since profiling was enabled
+    long long prof_seen = 0;   // forwards issued since then
+    int prof_every = 1;        // every prof_every-th forward is recorded
     hipEvent_t ev[kProfRing][MOE_N_PHASES + 1] = {};
     moe_config_t cfg;
     moe_buffers_t buf;
@@ -200,6 +202,12 @@ void moe_layer_destroy(moe_layer_t *layer)
 moe_status_t moe_profile_enable(moe_layer_t *l, int32_t enable)
 {
     if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    if (enable < 0) return fail(MOE_ERR_ARG, "enable %d is negative", enable);
+    if (enable && l->prof_on) {   // only the sampling changes
+        l->prof_every = enable;
+        l->prof_seen = 0;          // the next forward is recorded
+        return MOE_OK;
+    }
     if ((enable != 0) == l->prof_on) return MOE_OK;
     if (enable) {
         for (int i = 0; i < kProfRing; ++i)
@@ -213,6 +221,8 @@ moe_status_t moe_profile_enable(moe_layer_t *l, int32_t enable)
                 }
             }
         l->prof_count = 0;
+        l->prof_seen = 0;
+        l->prof_every = enable;
         l->prof_on = true;
     } else {
         for (int i = 0; i < kProfRing; ++i)
@@ -453,7 +463,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.max_tiles = (int)(((long long)T * p.kk + tile_rows - 1) / tile_rows) + p.S;
 
     // optional phase events (benchmarks): event j is recorded before phase j, the last one after the pass
-    hipEvent_t *ev = l->prof_on ? l->ev[l->prof_count % kProfRing] : nullptr;
+    hipEvent_t *ev = l->prof_on && l->prof_seen++ % l->prof_every == 0 ? l->ev[l->prof_count % kProfRing] : nullptr;
     hipError_t e = hipSuccess;
     auto mark = [&](int j) { if (ev && e == hipSuccess) e = hipEventRecord(ev[j], st); };
     mark(MOE_PHASE_GATE);

@@ -192,7 +192,7 @@ def test_phase_timing_reports_every_phase():
     from paper_2510_02613_amd import binding as B
     wl = MoEWorkload(name="prof", tokens=300, **SMALL)
     case = _case(wl)
-    B.moe_profile_enable(case.layer.handle, True)
+    B.moe_profile_enable(case.layer.handle, 1)
     for _ in range(3):
         case.run()
     for back in range(3):
@@ -200,7 +200,15 @@ def test_phase_timing_reports_every_phase():
         assert len(ms) == 5 and all(0 <= v < 1000 for v in ms) and sum(ms) > 0
     with pytest.raises(B.MoEError):
         B.moe_profile_read(case.layer.handle, 3)
-    B.moe_profile_enable(case.layer.handle, False)
+    # sampling: of the next 7 forwards the 1st, 4th and 7th are recorded
+    B.moe_profile_enable(case.layer.handle, 3)
+    for _ in range(7):
+        case.run()
+    for back in range(6):                       # 3 earlier + 3 sampled recordings
+        assert sum(B.moe_profile_read(case.layer.handle, back)) > 0
+    with pytest.raises(B.MoEError):
+        B.moe_profile_read(case.layer.handle, 6)
+    B.moe_profile_enable(case.layer.handle, 0)
     _full_check(case)
 
 
