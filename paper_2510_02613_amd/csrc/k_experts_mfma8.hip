@@ -104,26 +104,32 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
 // Issued as inline assembly on purpose: the compiler's wait-count insertion would otherwise
 // hold every later LDS read until these loads (which belong to a LATER stage) have returned.
 // Completion is awaited explicitly (wait_loads) before the step's barrier.
+// kStream: the line is marked non-temporal -- read once and not worth a place in L2.  Used for the weights
+// of the second GEMM: the rows y it writes are read back by the combine kernel right after, and
+// stay in cache when the weight stream does not push them out.
+template <bool kStream>
 __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, uint32_t lds_byte_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
+    if (kStream) asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
+    else         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
 // Loader roles: wavefronts 0-3 stream the weight rows (8 pieces each per weight step),
 // wavefronts 4-7 the token rows (up to 5 pieces each per K-step).  The split matters because a
 // wavefront's loads complete in order: a single wavefront issuing both could not keep two weight
 // steps in flight while waiting for the much younger token step.
+template <bool kStreamW>
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
     if (c.wave < 4) {
         const uint16_t *b = c.wbase + k0;
 #pragma unroll
-        for (int i = 0; i < kWPieces; ++i) dma_piece(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
+        for (int i = 0; i < kWPieces; ++i) dma_piece<kStreamW>(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
     } else {
         const uint16_t *b = c.abase + k0;
 #pragma unroll
         for (int i = 0; i < kXPieces; ++i)
-            if (i < c.xlive) dma_piece(b, c.off[i], slot_addr + ((c.wave & 3) + 4 * i) * 1024);
+            if (i < c.xlive) dma_piece<false>(b, c.off[i], slot_addr + ((c.wave & 3) + 4 * i) * 1024);
     }
 }
 
@@ -185,7 +191,7 @@ __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws,
     }
 }
 
-template <int NTC>
+template <int NTC, bool kStreamW>
 __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int KT, f32x16 (&acc)[kWT][kTC])
 {
     // KT K-steps of 32; weight steps cover two of them.  The caller issued weight steps 0, 1 and
@@ -215,9 +221,9 @@ __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int K
         }
         __syncthreads();  // everyone's share of step kt is in LDS; everyone is done reading step kt-1
         if (wloader) {
-            if (!half && ws + kNW - 1 < WT_) issue_step(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
+            if (!half && ws + kNW - 1 < WT_) issue_step<kStreamW>(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
         } else {
-            if (kt + kNX - 1 < KT) issue_step(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
+            if (kt + kNX - 1 < KT) issue_step<kStreamW>(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
         }
         multiply_stage<NTC>(c, ring + wslot * kWStage, ring + kNW * kWStage + xslot * kXStage, half, acc);
         if (half) { wslot = wslot + 1 == kNW ? 0 : wslot + 1; }
@@ -237,7 +243,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
         for (int t = 0; t < kTC; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-    k_loop<NTC>(c, ring, KT, acc);
+    k_loop<NTC, !kFirst>(c, ring, KT, acc);
     __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
 
     // ---- epilogue: accumulators -> private LDS region [token row][column] -> coalesced rows ----
@@ -371,8 +377,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     const int KT = K / kBK;
     {
         const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
-        if (c.wave < 4) { for (int s = 0; s < kNW - 1 && s < KT / 2; ++s) issue_step(c, wring + s * kWStage, s * kBKW); }
-        else            { for (int s = 0; s < kNX - 1 && s < KT; ++s) issue_step(c, xring + s * kXStage, s * kBK); }
+        if (c.wave < 4) { for (int s = 0; s < kNW - 1 && s < KT / 2; ++s) issue_step<!kFirst>(c, wring + s * kWStage, s * kBKW); }
+        else            { for (int s = 0; s < kNX - 1 && s < KT; ++s) issue_step<!kFirst>(c, xring + s * kXStage, s * kBK); }
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
