@@ -9,8 +9,9 @@
 // A token with no local assignment gets a zero row (partial sum for the
 // cross-rank reduction of expert parallelism, Sec. 2.1).
 //
-// One workgroup per token; each lane owns 16-byte column chunks so that every y
-// row and the out row are read / written fully coalesced.
+// A workgroup owns one token and every gridDim.y-th run of 256 16-byte column chunks of its row, so
+// that every y row and the out row are read / written fully coalesced; gridDim.y > 1 spreads a
+// decode-sized batch over the chip.
 #include "moe_internal.h"
 
 namespace emoe {
@@ -22,7 +23,7 @@ template <typename T> struct Chunk;
 template <> struct Chunk<uint16_t> { static constexpr int n = 8; };  // 8 bf16 = 16 B
 template <> struct Chunk<float> { static constexpr int n = 4; };     // 4 fp32 = 16 B
 
-template <typename T>
+template <typename T, bool kBatched>
 __global__ __launch_bounds__(256) void k_combine(Pass p)
 {
     constexpr int C = Chunk<T>::n;
@@ -37,10 +38,32 @@ __global__ __launch_bounds__(256) void k_combine(Pass p)
     __syncthreads();
     const T *y = (const T *)p.y;
     T *out = (T *)p.out + (size_t)t * p.H;
-    for (int c = threadIdx.x * C; c < p.H; c += 256 * C) {
-        float acc[C];
+    for (int c = (blockIdx.y * 256 + threadIdx.x) * C; c < p.H; c += gridDim.y * 256 * C) {
+    float acc[C];
 #pragma unroll
-        for (int i = 0; i < C; ++i) acc[i] = 0.f;
+    for (int i = 0; i < C; ++i) acc[i] = 0.f;
+    if (kBatched) {
+        // few tokens: the rows of four assignments are requested before any is added (the loads are
+        // independent, only the additions are ordered), since there is no other workgroup to hide them
+        for (int j0 = 0; j0 < p.kk; j0 += 4) {
+            uint4 raw[4];
+            float wj[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = j0 + u < p.kk ? rows[j0 + u] : -1;
+                // an assignment that is not local contributes weight 0 times zeros (nothing is read for it)
+                raw[u] = make_uint4(0, 0, 0, 0);
+                if (r >= 0) raw[u] = *(const uint4 *)(y + (size_t)r * p.H + c);
+                wj[u] = r < 0 ? 0.f : wts[j0 + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const T *v = (const T *)&raw[u];
+#pragma unroll
+                for (int i = 0; i < C; ++i) acc[i] = fmaf(wj[u], load_f32<T>(v, i), acc[i]);
+            }
+        }
+    } else {
         for (int j = 0; j < p.kk; ++j) {
             const int r = rows[j];
             if (r < 0) continue;
@@ -50,11 +73,12 @@ __global__ __launch_bounds__(256) void k_combine(Pass p)
 #pragma unroll
             for (int i = 0; i < C; ++i) acc[i] = fmaf(wj, load_f32<T>(v, i), acc[i]);
         }
-        uint4 o;
-        T *ov = (T *)&o;
+    }
+    uint4 o;
+    T *ov = (T *)&o;
 #pragma unroll
-        for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[i]);
-        *(uint4 *)(out + c) = o;
+    for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[i]);
+    *(uint4 *)(out + c) = o;
     }
 }
 
@@ -84,8 +108,17 @@ hipError_t launch_copy(void *dst, const void *src, size_t bytes, int blocks, hip
 
 hipError_t launch_combine(const Pass &p, hipStream_t st)
 {
-    if (p.act_bf16) hipLaunchKernelGGL((k_combine<uint16_t>), dim3(p.T), dim3(256), 0, st, p);
-    else            hipLaunchKernelGGL((k_combine<float>), dim3(p.T), dim3(256), 0, st, p);
+    // a row is shared out over several workgroups only while there are too few tokens to fill the chip
+    const int per = 256 * (p.act_bf16 ? 8 : 4);
+    const int ny = p.T >= 1024 ? 1 : (p.H + per - 1) / per;
+    const bool few = p.T < 1024;
+    if (p.act_bf16) {
+        if (few) hipLaunchKernelGGL((k_combine<uint16_t, true>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else     hipLaunchKernelGGL((k_combine<uint16_t, false>), dim3(p.T, ny), dim3(256), 0, st, p);
+    } else {
+        if (few) hipLaunchKernelGGL((k_combine<float, true>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else     hipLaunchKernelGGL((k_combine<float, false>), dim3(p.T, ny), dim3(256), 0, st, p);
+    }
     return hipGetLastError();
 }
 
