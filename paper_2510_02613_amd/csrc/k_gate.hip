@@ -354,9 +354,13 @@ __global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
     // K range of this wavefront (whole chunks of 128)
     int kbeg = 0, kend = H;
     if (KSPLIT) {
-        const int chunks = (H + 127) / 128, per = (chunks + 3) / 4;
-        kbeg = min(H, wave * per * 128);
-        kend = min(H, (wave + 1) * per * 128);
+        // workgroup z of gridDim.z takes an equal share of the chunks (its sums go to plane z of the
+        // logits buffer), its wavefronts a quarter of that each
+        const int chunks = (H + 127) / 128;
+        const int c0 = (int)((long long)blockIdx.z * chunks / gridDim.z), c1 = (int)((long long)(blockIdx.z + 1) * chunks / gridDim.z);
+        const int per = (c1 - c0 + 3) / 4;
+        kbeg = min(H, min(c1, c0 + wave * per) * 128);
+        kend = min(H, min(c1, c0 + (wave + 1) * per) * 128);
     }
 
     const uint16_t *xrow[TT];
@@ -443,6 +447,8 @@ __global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
                 }
     }
     // lane holds token n of each token tile, experts 4q + r of each of its expert tiles
+    float *plane = p.logits + (size_t)blockIdx.z * p.T * E;
+    const float *bias = blockIdx.z == 0 ? p.logit_bias : nullptr;   // added once
 #pragma unroll
     for (int a = 0; a < ET; ++a)
 #pragma unroll
@@ -452,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void k_gate_logits(Pass p)
             if (t < p.T) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (e + r < E) p.logits[(size_t)t * E + e + r] = acc[a][tb][r] + (p.logit_bias ? p.logit_bias[e + r] : 0.f);
+                    if (e + r < E) plane[(size_t)t * E + e + r] = acc[a][tb][r] + (bias ? bias[e + r] : 0.f);
             }
         }
 }
@@ -634,10 +640,10 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
 }
 
 template <typename WT, int TT, int ET, bool KSPLIT>
-hipError_t launch_gate_logits_t(const Pass &p, hipStream_t st)
+hipError_t launch_gate_logits_t(const Pass &p, int planes, hipStream_t st)
 {
     const int eb = (KSPLIT ? 1 : 4) * ET * 16;
-    dim3 grid((p.T + 16 * TT - 1) / (16 * TT), (p.E + eb - 1) / eb);
+    dim3 grid((p.T + 16 * TT - 1) / (16 * TT), (p.E + eb - 1) / eb, planes);
     hipLaunchKernelGGL((k_gate_logits<WT, TT, ET, KSPLIT>), grid, dim3(kThreads), 0, st, p);
     return hipGetLastError();
 }
@@ -653,7 +659,12 @@ hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
     // batch size; the LDS-tiled kernel needs a few thousand tokens before its per-workgroup K loop stops
     // being the critical path.  Measured crossover: about 128 MB of router re-reads.
     const size_t router_rereads = (size_t)((p.T + 15) / 16) * p.E * p.H * (p.router_bf16 ? 2 : 4);
-    if (!p.gate_tiled && (p.T <= 256 || router_rereads <= (size_t)128 << 20)) e = launch_gate_logits_t<WT, 1, 1, true>(p, st);
+    if (!p.gate_tiled && (p.T <= 256 || router_rereads <= (size_t)128 << 20)) {
+        // a decode-sized batch has few (token, expert) tiles: the contraction is shared out over workgroups
+        // as well, 4 chunks of 128 (one per wavefront) or more each
+        if (p.T <= 256) planes = min(kGatePlanes, max(1, (p.H + 127) / 128 / 4));
+        e = launch_gate_logits_t<WT, 1, 1, true>(p, planes, st);
+    }
     else if (gate_dma_supports(p))      e = launch_gate_logits_dma(p, &planes, st);    // LDS ring filled by direct copies
     else if (p.E > 64 && p.T >= 8192)   e = launch_gate_logits_lds<WT, 4, 2>(p, st);   // 64 tokens x 128 experts
     else                                e = launch_gate_logits_lds<WT, 2, 1>(p, st);   // 32 tokens x 64 experts
