@@ -653,15 +653,15 @@ hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
 {
     Pass p = p0;
     int planes = 1;
-    // pick the split that gives the chip enough workgroups
     hipError_t e;
-    // The K-split kernel re-reads the router once per 16-token block (from L2) but fills the chip at any
-    // batch size; the LDS-tiled kernel needs a few thousand tokens before its per-workgroup K loop stops
-    // being the critical path.  Measured crossover: about 128 MB of router re-reads.
+    // Up to a hundred or so tokens there are too few (token, expert) tiles for the LDS-tiled kernels: the
+    // K-split kernel reads both operands straight into registers, 16 tokens x 16 experts per workgroup, and
+    // shares the contraction out over its wavefronts and over workgroups.  (Without the direct-to-LDS
+    // kernel -- H not a multiple of 64 -- it stays ahead until the router re-reads reach about 128 MB.)
     const size_t router_rereads = (size_t)((p.T + 15) / 16) * p.E * p.H * (p.router_bf16 ? 2 : 4);
-    if (!p.gate_tiled && (p.T <= 256 || router_rereads <= (size_t)128 << 20)) {
-        // a decode-sized batch has few (token, expert) tiles: the contraction is shared out over workgroups
-        // as well, 4 chunks of 128 (one per wavefront) or more each
+    const bool small = gate_dma_supports(p) ? p.T <= 128 : (p.T <= 256 || router_rereads <= (size_t)128 << 20);
+    if (!p.gate_tiled && small) {
+        // 4 chunks of 128 (one per wavefront) or more per workgroup
         if (p.T <= 256) planes = min(kGatePlanes, max(1, (p.H + 127) / 128 / 4));
         e = launch_gate_logits_t<WT, 1, 1, true>(p, planes, st);
     }
