@@ -250,6 +250,9 @@ def main():
             sys.exit(2)
         result["scale_while_serve"] = scale_while_serve(torch, layer, wl, inp, x, out, stream, args)
 
+    if wl.name == "qwen3_relayout":
+        result["relayout"] = relayout_report(torch, layer, wl, inp, x, out, stream, w13_pool, w2_pool)
+
     if args.replicate_hot is not None:
         if wl.name != "qwen3_relayout" or not 0 < args.replicate_hot <= wl.n_slots // 2:
             print("bench.py: --replicate-hot N needs --workload qwen3_relayout and 0 < N <= %d" % (wl.n_slots // 2), file=sys.stderr)
@@ -313,6 +316,77 @@ def scale_while_serve(torch, layer, wl, inp, x, out, stream, args):
             "window_ms": busy * n, "window_ms_with_copies_running": overlap_ms,
             "fill_bytes": nbytes, "fill_ms": fill_ms, "fill_gbs": nbytes / (fill_ms * 1e-3) / 1e9,
             "ms_per_step_phase_b_after_switch": after}
+
+
+def relayout_report(torch, layer, wl, inp, x, out, stream, w13_pool_b, w2_pool_b):
+    """The re-layout workload on its three placements, 16 forwards each after 3 warm-ups: phase A (experts
+    0..31 resident), phase B (64 resident, the new 32 in shuffled slots: the placement the timed region ran
+    on), and phase B with the new experts in slot order (what a freshly built contiguous layout would be).
+    Also what the switches changed: nothing but the table (pool and workspace addresses, free device memory)."""
+    from workloads import relayout_maps, build_slot_pool
+    map_a, map_b = relayout_maps(wl)
+    half = wl.n_slots // 2
+    map_c = map_b.copy()
+    map_c[half:2 * half] = np.arange(half, 2 * half, dtype=np.int32)     # contiguous: expert e in slot e
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ptrs = (layer.w13.data_ptr(), layer.w2.data_ptr(), layer.workspace.data_ptr())
+    free0, _ = torch.cuda.mem_get_info()
+
+    def timed(n=16):
+        for _ in range(3):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        e0.record(stream)
+        for _ in range(n):
+            layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        counts = layer.view(wl.tokens)["counts"]
+        work = algorithmic_work(wl, counts, 0)
+        return {"ms_per_step": ms, "assignments": work["assignments"], "active_slots": work["active_slots"],
+                "assignments_per_s": work["assignments"] / (ms * 1e-3),
+                "tflops": work["flops_total"] / (ms * 1e-3) / 1e12,
+                "min_hbm_gbs": work["bytes_layer_min"] / (ms * 1e-3) / 1e9}
+
+    rep = {}
+    layer.set_expert_map(map_a)                       # the weights of phase B's pool hold phase A's experts in place
+    rep["phase_a_32_experts"] = timed()
+    layer.set_expert_map(map_b)
+    first_b = timed()
+    out_b = out.clone()
+    free1, _ = torch.cuda.mem_get_info()              # before the slot-order pool is staged for the comparison
+    same = ptrs == (layer.w13.data_ptr(), layer.w2.data_ptr(), layer.workspace.data_ptr())
+    # the two phase-B placements alternate three times (device-side pool copies), so that drift of the
+    # box between the measurements is not read as a difference between them
+    pool_b = (layer.w13.clone(), layer.w2.clone())
+    pool_c = (layer.upload(build_slot_pool(inp["w13_experts"], map_c, wl.n_slots, wl.n_local, ())),
+              layer.upload(build_slot_pool(inp["w2_experts"], map_c, wl.n_slots, wl.n_local, ())))
+    runs_b, runs_c = [first_b], []
+    identical = True
+    for rnd in range(3):
+        layer.w13.copy_(pool_c[0]); layer.w2.copy_(pool_c[1])
+        layer.set_expert_map(map_c)
+        runs_c.append(timed())
+        identical = identical and bool(torch.equal(out_b, out))
+        layer.w13.copy_(pool_b[0]); layer.w2.copy_(pool_b[1])
+        layer.set_expert_map(map_b)                   # ends on the placement of the timed region
+        if rnd < 2:
+            runs_b.append(timed())
+
+    def mean(runs):
+        m = dict(runs[0])
+        for key in ("ms_per_step", "assignments_per_s", "tflops", "min_hbm_gbs"):
+            m[key] = float(np.mean([r[key] for r in runs]))
+        m["ms_per_step_runs"] = [r["ms_per_step"] for r in runs]
+        return m
+
+    rep["phase_b_64_experts_shuffled_slots"] = mean(runs_b)
+    rep["phase_b_64_experts_slot_order"] = mean(runs_c)
+    rep["outputs_identical_shuffled_vs_slot_order"] = identical
+    rep["pool_and_workspace_addresses_unchanged"] = bool(same)
+    rep["device_memory_taken_by_the_switches_bytes"] = int(free0 - free1)
+    torch.cuda.synchronize()
+    return rep
 
 
 def replicate_hot(torch, layer, wl, x, out, stream, n_hot):
