@@ -631,8 +631,14 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
     const int t = blockIdx.x * 4 + wave;
     if (t >= p.T) return;
     for (int e = lane; e < E; e += 64) {
-        float v = p.logits[(size_t)t * E + e];
-        for (int z = 1; z < p.logit_planes; ++z) v += p.logits[((size_t)z * p.T + t) * E + e];   // partial sums, in K order
+        // partial sums of the K ranges: all planes are requested at once, then added in K order
+        float part[kGatePlanes];
+#pragma unroll
+        for (int z = 0; z < kGatePlanes; ++z) part[z] = z < p.logit_planes ? p.logits[((size_t)z * p.T + t) * E + e] : 0.f;
+        float v = part[0];
+#pragma unroll
+        for (int z = 1; z < kGatePlanes; ++z)
+            if (z < p.logit_planes) v += part[z];
         lg[e] = v;
     }
     wave_sync();
