@@ -65,6 +65,7 @@ constexpr int kWPieces = kWStage / 1024 / 4;   // 8: 1 KB pieces (8 rows x 128 B
 constexpr int kXPieces = kXStage / 1024 / 4;   // 5: 1 KB pieces (16 rows x 64 B) per token-loader wavefront per K-step
 constexpr int kRingBytes = kNW * kWStage + kNX * kXStage;
 constexpr int kXcds = 8;
+constexpr int kMaxPartialSets = 256;        // partial-sum sets the workspace has room for: one round of a 256-unit chip
 constexpr int kTC = kMaxTT / 2;            // token tiles per wavefront
 constexpr int kWT = 2;                     // weight tiles per wavefront
 constexpr int kEpiStride1 = 2 * kWT * 16 + 8;   // GEMM-1: 32 h columns per wavefront, bytes per staged row
@@ -233,8 +234,21 @@ __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int K
     }
 }
 
-template <bool kFirst, int NTC>
-__device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, int KT, char *ring)
+// Partial sums of a tile whose contraction is shared out over several workgroups (the tail of a
+// launch, see the kernel): floats per set, and where a wavefront's accumulator registers go.
+constexpr int kPartialFloats = kWaves * kWT * kTC * 16 * 64;   // 81920 = 320 KB
+__device__ __forceinline__ float *partial_at(float *set, int wave, int a, int t, int r4, int lane)
+{
+    return set + ((((wave * kWT + a) * kTC + t) * 4 + r4) * 64 + lane) * 4;   // 16 bytes per lane, 1 KB per instruction
+}
+
+// kPhase 0: a whole tile.  1: the partial sums of one of n_parts K ranges of a tile, left in
+// p.partials.  2: the sum of a tile's partial sums, in K order, then the same epilogue as phase 0.
+// (Letting the last of a tile's workgroups to finish do the adding, in the same launch, was
+// measured and is slower: the device-wide fence it needs costs more than the third launch.)
+template <bool kFirst, int NTC, int kPhase>
+__device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, int KT, char *ring,
+                                          float *tile_sets, int part, int n_parts)
 {
     f32x16 acc[kWT][kTC];
 #pragma unroll
@@ -243,8 +257,37 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
         for (int t = 0; t < kTC; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-    k_loop<NTC, !kFirst>(c, ring, KT, acc);
-    __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
+    if (kPhase != 2) {
+        k_loop<NTC, !kFirst>(c, ring, KT, acc);
+        __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
+    }
+    if (kPhase == 1) {
+        float *mine = tile_sets + (size_t)part * kPartialFloats;
+#pragma unroll
+        for (int a = 0; a < kWT; ++a)
+#pragma unroll
+            for (int t = 0; t < NTC; ++t)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    float4 v = make_float4(acc[a][t][r4 * 4], acc[a][t][r4 * 4 + 1], acc[a][t][r4 * 4 + 2], acc[a][t][r4 * 4 + 3]);
+                    *(float4 *)partial_at(mine, c.wave, a, t, r4, c.lane) = v;
+                }
+        return;
+    }
+    if (kPhase == 2) {
+        for (int q = 0; q < n_parts; ++q) {
+            float *set = tile_sets + (size_t)q * kPartialFloats;
+#pragma unroll
+            for (int a = 0; a < kWT; ++a)
+#pragma unroll
+                for (int t = 0; t < NTC; ++t)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const float4 v = *(const float4 *)partial_at(set, c.wave, a, t, r4, c.lane);
+                        acc[a][t][r4 * 4] += v.x; acc[a][t][r4 * 4 + 1] += v.y; acc[a][t][r4 * 4 + 2] += v.z; acc[a][t][r4 * 4 + 3] += v.w;
+                    }
+        }
+    }
 
     // ---- epilogue: accumulators -> private LDS region [token row][column] -> coalesced rows ----
     constexpr int COLS = kFirst ? kWT * 16 : kWT * 32;      // output columns of this wavefront
@@ -291,7 +334,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
     }
 }
 
-template <bool kFirst>
+template <bool kFirst, int kPhase>
 __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
 {
     const int K = kFirst ? p.H : p.I;
@@ -314,7 +357,38 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
         if (n_ntiles % d == 0 && (dealt - units) * 20 <= units) { g = d; break; }
     }
     const int spp = n_ntiles / g;                      // N-slices per unit
-    const int b = blockIdx.x;
+
+    // The tail of the launch.  Workgroups run in rounds of one per compute unit; with long
+    // contractions a launch is only a few rounds deep, and a last round that fills a fraction of the
+    // chip costs a whole round.  When the launch allows it (p.k_split), the workgroups of that last
+    // round are run separately: each tile's contraction is shared out over n_parts workgroups
+    // (phase 1, partial sums to p.partials), which a third launch adds up in K order (phase 2).  The
+    // split is a function of the tile list alone, so all three launches agree on it.
+    const int rows_total = (n_chunks * g + kXcds - 1) / kXcds * spp;   // rows of 8 workgroups, holes of the last unit row included
+    const int rows_round = min(p.n_cus, kMaxPartialSets) / kXcds;
+    int tail_rows = 0, n_parts = 1;
+    if (p.k_split && rows_total >= rows_round) {
+        const int tr = rows_total % rows_round;
+        int parts = tr ? rows_round / tr : 1;
+        parts = min(parts, min(8, K / kBKW / 8));       // eight weight steps or more per part
+        if (parts >= 2) { tail_rows = tr; n_parts = parts; }
+    }
+    const int head_blocks = (rows_total - tail_rows) * kXcds;
+    int b, part = 0;
+    if (kPhase == 0) {
+        b = blockIdx.x;
+        if (b >= head_blocks) return;
+    } else if (kPhase == 1) {
+        const int tail_blocks = tail_rows * kXcds;
+        if (tail_blocks == 0) return;
+        part = blockIdx.x / tail_blocks;
+        if (part >= n_parts) return;
+        b = head_blocks + blockIdx.x % tail_blocks;     // consecutive workgroups keep their XCDs (tail_blocks is a multiple of 8)
+    } else {
+        if ((int)blockIdx.x >= tail_rows * kXcds) return;
+        b = head_blocks + blockIdx.x;
+    }
+    float *tile_sets = kPhase == 0 ? nullptr : p.partials + (size_t)((b - head_blocks) * n_parts) * kPartialFloats;
     const int j = b / kXcds;
     const int unit = (j / spp) * kXcds + b % kXcds;
     const int chunk = unit / g;
@@ -332,10 +406,14 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     c.xlive = c.wave < 4 ? 0 : min(kXPieces, max(0, (2 * c.n_tt - (c.wave & 3) + 3) >> 2));  // pieces w, w+4, ... < 2*n_tt
 
     // ---- staging plan ----
+    // this workgroup's K range: everything, or (phase 1) weight steps [w0, w1) of the tile
+    const int wsteps = K / kBKW;
+    const int w0 = kPhase == 1 ? (int)((long long)part * wsteps / n_parts) : 0;
+    const int w1 = kPhase == 1 ? (int)((long long)(part + 1) * wsteps / n_parts) : wsteps;
     const uint16_t *W = (const uint16_t *)(kFirst ? p.w13 : p.w2) + (size_t)mt.slot * (kFirst ? 2 : 1) * (size_t)p.I * p.H;
     const uint16_t *A = (const uint16_t *)(kFirst ? p.x : p.h);
-    c.wbase = W;
-    c.abase = A;
+    c.wbase = W + w0 * kBKW;      // rows are K-contiguous: the piece offsets below are relative to the range's first k
+    c.abase = A + w0 * kBKW;
     if (c.wave < 4) {
 #pragma unroll
         for (int i = 0; i < kWPieces; ++i) {
@@ -374,8 +452,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
         for (int ks = 0; ks < kBK / 16; ++ks) c.xoff[ks] = xr * 64 + (((ks * 2 + khalf) ^ swz(xr)) << 4);
     }
 
-    const int KT = K / kBK;
-    {
+    const int KT = (w1 - w0) * (kBKW / kBK);
+    if (kPhase != 2) {
         const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
         if (c.wave < 4) { for (int s = 0; s < kNW - 1 && s < KT / 2; ++s) issue_step<!kFirst>(c, wring + s * kWStage, s * kBKW); }
         else            { for (int s = 0; s < kNX - 1 && s < KT; ++s) issue_step<!kFirst>(c, xring + s * kXStage, s * kBK); }
@@ -384,12 +462,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
     const int ntc = (c.n_tt - c.wm + 1) >> 1;
     switch (ntc) {
-    case 5: wave_body<kFirst, 5>(p, c, mt, n0, N, KT, ring); break;
-    case 4: wave_body<kFirst, 4>(p, c, mt, n0, N, KT, ring); break;
-    case 3: wave_body<kFirst, 3>(p, c, mt, n0, N, KT, ring); break;
-    case 2: wave_body<kFirst, 2>(p, c, mt, n0, N, KT, ring); break;
-    case 1: wave_body<kFirst, 1>(p, c, mt, n0, N, KT, ring); break;
-    default: wave_body<kFirst, 0>(p, c, mt, n0, N, KT, ring); break;
+    case 5: wave_body<kFirst, 5, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    case 4: wave_body<kFirst, 4, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    case 3: wave_body<kFirst, 3, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    case 2: wave_body<kFirst, 2, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    case 1: wave_body<kFirst, 1, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    default: wave_body<kFirst, 0, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
     }
 }
 
@@ -400,16 +478,38 @@ int mfma8_tile_rows() { return kBM; }
 // usable when both contraction lengths are whole K-steps (direct-to-LDS loads cannot zero fill)
 bool mfma8_supports(const Pass &p) { return p.act_bf16 && p.H % kBKW == 0 && p.I % kBKW == 0; }
 
-hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st)
+size_t mfma8_partial_bytes() { return (size_t)kMaxPartialSets * kPartialFloats * sizeof(float); }
+
+hipError_t launch_experts_mfma8(const Pass &p0, int which, hipStream_t st)
 {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        cus = n >= kXcds ? n : kXcds;
+    }
+    Pass p = p0;
+    p.n_cus = cus;
+    // sharing out the contraction of the last round's tiles pays when a tile is long: 64 weight steps or more
+    const int K = which == 0 ? p.H : p.I;
+    p.k_split = p.partials != nullptr && K / kBKW >= 64;
+    const int nt = which == 0 ? (p.I + kBN / 2 - 1) / (kBN / 2) : (p.H + kBN - 1) / kBN;
+    const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
+    const int round_blocks = (cus < kMaxPartialSets ? cus : kMaxPartialSets) / kXcds * kXcds;
     if (which == 0) {
-        const int nt = (p.I + kBN / 2 - 1) / (kBN / 2);
-        const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
-        hipLaunchKernelGGL((k_expert_gemm_mfma8<true>), dim3(grid), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 0>), dim3(grid), dim3(kThreads), 0, st, p);
+        if (p.k_split) {
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 1>), dim3(round_blocks), dim3(kThreads), 0, st, p);
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 2>), dim3(round_blocks / 2), dim3(kThreads), 0, st, p);
+        }
     } else {
-        const int nt = (p.H + kBN - 1) / kBN;
-        const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
-        hipLaunchKernelGGL((k_expert_gemm_mfma8<false>), dim3(grid), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 0>), dim3(grid), dim3(kThreads), 0, st, p);
+        if (p.k_split) {
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 1>), dim3(round_blocks), dim3(kThreads), 0, st, p);
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 2>), dim3(round_blocks / 2), dim3(kThreads), 0, st, p);
+        }
     }
     return hipGetLastError();
 }

@@ -45,7 +45,8 @@ constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: siz
 
 // Offsets of every intermediate inside the workspace.
 struct Layout {
-    size_t map[2], logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, total;
+    size_t map[2], logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
+    bool has_partials;
 };
 
 size_t esize(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
@@ -105,6 +106,10 @@ Layout make_layout(const moe_config_t &c)
     L.n_tiles = take(4);
     L.h = take(esize(c.act_dtype) * A * c.inter);
     L.y = take(esize(c.act_dtype) * A * c.hidden);
+    // partial sums of split tiles: only layers whose large-tile GEMMs can have contractions long enough to split
+    L.has_partials = c.act_dtype == MOE_BF16 && c.hidden % 64 == 0 && c.inter % 64 == 0 && (c.hidden >= 4096 || c.inter >= 4096) &&
+                     (long long)A >= 48ll * S;
+    L.partials = take(L.has_partials ? mfma8_partial_bytes() : 0);
     L.total = o;
     return L;
 }
@@ -451,6 +456,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.n_tiles = (int32_t *)(ws + l->lay.n_tiles);
     p.h = ws + l->lay.h;
     p.y = ws + l->lay.y;
+    p.partials = l->lay.has_partials ? (float *)(ws + l->lay.partials) : nullptr;
 
     p.gate_tiled = (flags & MOE_FLAG_GATE_TILED) != 0;
     const bool identity = flags & MOE_FLAG_IDENTITY_EXPERTS;

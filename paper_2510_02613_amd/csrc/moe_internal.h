@@ -51,6 +51,9 @@ struct Pass {
     void *y;             // [A,H]
     int32_t max_tiles;
     int32_t gate_tiled;  // the LDS-tiled gate logits kernel is forced (testing aid)
+    float *partials;     // partial sums of the large-tile GEMMs' split tiles, or NULL (no room: never split)
+    int32_t n_cus;       // compute units of the device (set by the large-tile launcher)
+    int32_t k_split;     // this launch may share the contraction of its last round's tiles out (set by the launcher)
 };
 
 constexpr int kGatePlanes = 8;         // partial-sum planes of the gate logits the workspace has room for
@@ -70,6 +73,7 @@ int mfma_tile_rows();
 hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st);
 int mfma8_tile_rows();
 bool mfma8_supports(const Pass &p);
+size_t mfma8_partial_bytes();   // workspace for the partial sums of tiles whose contraction is shared out
 hipError_t launch_ceiling_mfma(int blocks, int iters, int random_operands, float *sink, hipStream_t st);
 double ceiling_mfma_flops(int blocks, int iters);
 hipError_t launch_ceiling_stream(const void *buf, size_t bytes, float *sink, hipStream_t st);

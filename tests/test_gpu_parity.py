@@ -147,6 +147,18 @@ def test_dsv3_rank_full_size_sampled():
     _full_check(case, sample=64)
 
 
+def test_long_contraction_with_a_split_last_round():
+    """288 one-chunk groups x one N-slice = 36 rows of 8 workgroups on a 32-row chip: the 4 rows of the last
+    round have their contraction (H = 4096) shared out over 8 workgroups each and summed by a third launch.
+    Rows of every group are sampled, so tiles of the whole rounds and of the split round are both graded."""
+    wl = MoEWorkload(name="splitk", tokens=1800, hidden=4096, inter=64, n_experts=288, top_k=8, n_slots=288,
+                     n_local=288, act_dtype="bf16", router_dtype="bf16", gate="softmax", seed=17)
+    case = _case(wl)
+    _, v, _ = _full_check(case, sample=160)
+    assert len(v["tiles"]) == 288 and v["counts"].min() > 0      # the launch shape the test is about
+    assert wl.tokens * wl.top_k >= 48 * wl.n_slots               # ... on the large-tile kernels
+
+
 def test_dsv2_lite_shape_full_size_sampled():
     """third model shape of the paper's evaluation: 64 experts, top-6, no renormalisation, 2 shared experts"""
     _full_check(_case(get_workload("dsv2_lite")), sample=64)
