@@ -196,7 +196,9 @@ template <int NTC, bool kStreamW>
 __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int KT, f32x16 (&acc)[kWT][kTC])
 {
     // KT K-steps of 32; weight steps cover two of them.  The caller issued weight steps 0, 1 and
-    // token steps 0, 1 (those that exist).
+    // token steps 0, 1 (those that exist).  Weight step ws + 2 is issued at the end of the second
+    // K-step of weight step ws, into the slot of weight step ws - 1, which every wavefront left at
+    // the barrier before that K-step.
     const bool wloader = c.wave < 4;
     const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
     const int WT_ = KT / 2;                                    // weight steps
@@ -221,14 +223,19 @@ __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int K
             }
         }
         __syncthreads();  // everyone's share of step kt is in LDS; everyone is done reading step kt-1
-        if (wloader) {
-            if (!half && ws + kNW - 1 < WT_) issue_step<kStreamW>(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
-        } else {
-            if (kt + kNX - 1 < KT) issue_step<kStreamW>(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
-        }
+        if (!wloader && kt + kNX - 1 < KT) issue_step<kStreamW>(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
         multiply_stage<NTC>(c, ring + wslot * kWStage, ring + kNW * kWStage + xslot * kXStage, half, acc);
-        if (half) { wslot = wslot + 1 == kNW ? 0 : wslot + 1; }
-        else      { wfill = wfill + 1 == kNW ? 0 : wfill + 1; }
+        // The next weight step goes out AFTER the multiply of the second half of a weight step, not
+        // right after the barrier: the compute unit returns copies in the order they were issued, so
+        // token copies (L2 hits, needed two K-steps on) issued just behind a burst of weight copies
+        // wait out that burst's HBM latency.  Issued here -- the weight loaders reach the barrier
+        // early anyway -- the burst falls between two rounds of token copies, with most of a K-step
+        // to the next one (qwen3 GEMM-1 276 -> 265 us, GEMM-2 166 -> 156 us).
+        if (half) {
+            if (wloader && ws + kNW - 1 < WT_) issue_step<kStreamW>(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
+            wslot = wslot + 1 == kNW ? 0 : wslot + 1;
+            wfill = wfill + 1 == kNW ? 0 : wfill + 1;
+        }
         xslot = xslot + 1 == kNX ? 0 : xslot + 1;
         xfill = xfill + 1 == kNX ? 0 : xfill + 1;
     }
