@@ -10,10 +10,12 @@
 //    compute unit has to hold ~48 KB of weight bytes in flight to cover HBM latency
 //    at full bandwidth, and HBM delivers whole 128-byte lines much faster than half
 //    lines.  The weight rows therefore travel in steps of 64 k (one full line per
-//    row, 32 KB per step) through their own 3-deep ring, two steps in flight, beside
-//    a 3-deep ring of token steps of 32 k (those come from L2); each ring has its own
-//    loader wavefronts, because a wavefront's loads complete in order and the two
-//    streams run at different distances.  Only the OLDEST step of a ring is waited for.
+//    row, 32 KB per step) through their own 3-deep ring, beside a 3-deep ring of
+//    token steps of 32 k (those come from L2); each ring has its own loader
+//    wavefronts, because a wavefront's loads complete in order and the two streams
+//    run at different distances.  Only the OLDEST step of a ring is waited for, and
+//    a weight step is issued late in a K-step, between two rounds of token copies
+//    (see k_loop: a compute unit returns copies in issue order).
 //  * A compute unit pulls ~64 B/clk from L2 but retires 4096 bf16 flops/clk, so a
 //    tile must reuse staged bytes >= 64 times: up to 320 token rows x 256 weight
 //    rows gives 114-142 (a 128 x 128 tile gives exactly 64 and is bandwidth bound).
