@@ -8,14 +8,14 @@
 //  * Every expert's weights are used by only ~256 rows, so the layer streams all
 //    resident weights from HBM once per pass: the kernel must keep HBM busy.  A
 //    compute unit has to hold ~48 KB of weight bytes in flight to cover HBM latency
-//    at full bandwidth, and HBM delivers whole 128-byte lines much faster than half
-//    lines.  The weight rows therefore travel in steps of 64 k (one full line per
-//    row, 32 KB per step) through their own 3-deep ring, beside a 3-deep ring of
-//    token steps of 32 k (those come from L2); each ring has its own loader
-//    wavefronts, because a wavefront's loads complete in order and the two streams
-//    run at different distances.  Only the OLDEST step of a ring is waited for, and
-//    a weight step is issued late in a K-step, between two rounds of token copies
-//    (see k_loop: a compute unit returns copies in issue order).
+//    at full bandwidth, and whole 128-byte lines travel much faster than half lines
+//    (also out of L2: a copy instruction that touches 16 half lines costs the issuing
+//    wavefront twice one that touches 8 whole lines).  Both operands therefore travel
+//    in steps of 64 k -- one full line per row: 32 KB of weight rows, up to 40 KB of
+//    token rows per step -- through a 2-deep ring each, with their own loader
+//    wavefronts.  The weight step is issued half way through a K-step's multiply,
+//    between two rounds of token copies (see k_loop: a compute unit returns copies in
+//    issue order).
 //  * A compute unit pulls ~64 B/clk from L2 but retires 4096 bf16 flops/clk, so a
 //    tile must reuse staged bytes >= 64 times: up to 320 token rows x 256 weight
 //    rows gives 114-142 (a 128 x 128 tile gives exactly 64 and is bandwidth bound).
@@ -31,8 +31,8 @@
 // wavefronts per SIMD so that one's LDS waits hide under the other's MFMAs.
 //
 // Staging: global_load_lds_dwordx4 -- global memory straight into LDS, 16 bytes per
-// lane, no VGPR round trip, no ds_write.  One instruction fills 1 KB: 16 token rows
-// x 64 bytes or 8 weight rows x 128 bytes; lane i lands in 16-byte slot i of the
+// lane, no VGPR round trip, no ds_write.  One instruction fills 1 KB: 8 rows of
+// 128 bytes (token rows or weight rows); lane i lands in 16-byte slot i of the
 // piece, so it FETCHES the chunk that belongs there: the XOR swizzle that keeps the
 // 16-byte operand reads conflict free is applied on the global side.
 //
@@ -51,7 +51,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBK = 32;                    // K-step: 64 bytes per tile row
+constexpr int kBK = 64;                    // K-step: 128 bytes per tile row, one whole cache line, for both operands
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
 constexpr int kBN = 256;                   // weight rows per workgroup
@@ -60,11 +60,11 @@ constexpr int kBM = kMaxTT * 32;           // 320: a whole group with its ragged
 constexpr int kRows = kBN + kBM;           // LDS rows per stage
 constexpr int kBKW = 64;                   // weight K-step: 128 bytes per row = one whole cache line
 constexpr int kWStage = kBN * kBKW * 2;    // 32 KB of weight rows per weight step
-constexpr int kXStage = kBM * kBK * 2;     // 20 KB of token rows per K-step
-constexpr int kNW = 3;                     // weight ring depth: 2 weight steps (64 KB) in flight from HBM
-constexpr int kNX = 3;                     // token ring depth: token rows come from L2
+constexpr int kXStage = kBM * kBK * 2;     // 40 KB of token rows per K-step
+constexpr int kNW = 2;                     // weight ring depth: one step multiplied, one in flight
+constexpr int kNX = 2;                     // token ring depth
 constexpr int kWPieces = kWStage / 1024 / 4;   // 8: 1 KB pieces (8 rows x 128 B) per weight-loader wavefront per weight step
-constexpr int kXPieces = kXStage / 1024 / 4;   // 5: 1 KB pieces (16 rows x 64 B) per token-loader wavefront per K-step
+constexpr int kXPieces = kXStage / 1024 / 4;   // 10: 1 KB pieces (8 rows x 128 B) per token-loader wavefront per K-step
 constexpr int kRingBytes = kNW * kWStage + kNX * kXStage;
 constexpr int kXcds = 8;
 constexpr int kMaxPartialSets = 256;        // partial-sum sets the workspace has room for: one round of a 256-unit chip
@@ -81,19 +81,16 @@ static_assert(kLdsBytes <= 160 * 1024, "LDS budget");
 // Everything one wavefront needs for its K loop.
 struct WaveCtx {
     const uint16_t *wbase, *abase;        // slot's weight matrix, activation matrix
-    uint32_t off[kWPieces];               // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
+    uint32_t off[kXPieces > kWPieces ? kXPieces : kWPieces];               // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
     uint32_t woff[kBKW / 16], xoff[kBK / 16]; // LDS byte offsets (inside a stage) of this lane's operand rows per sub-step
     int wave, lane, wm, wn, n_tt;
     int xlive;                            // token-loader wavefronts: how many of their pieces hold rows that exist
 };
 
-// 16-byte slot swizzle of a 64-byte tile row: slot = chunk ^ swz(row).  An LDS read of 16 bytes
-// per lane is served 16 lanes at a time over 64 four-byte banks (256 bytes, i.e. 4 rows): the
+// 16-byte slot swizzle of a 128-byte tile row: slot = chunk ^ swz8(row).  An LDS read of 16 bytes
+// per lane is served 16 lanes at a time over 64 four-byte banks (256 bytes, i.e. 2 rows): the
 // 16 consecutive rows a half-wavefront reads for one MFMA operand must therefore hit 16 distinct
-// 16-byte bank groups.  Row bits (2, 1^3) do that, and also keep any 8 consecutive rows apart on
-// a 32-bank view.
-__device__ __forceinline__ int swz(int row) { return (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1); }
-// The same for a 128-byte tile row (8 slots; 2 rows per 256 bytes): row bits (1, 2, 0^3).
+// 16-byte bank groups.  Row bits (1, 2, 0^3) do that.
 __device__ __forceinline__ int swz8(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
 
 // LDS byte address of a __shared__ object (LDS pointers are 32-bit offsets in address space 3).
@@ -117,10 +114,11 @@ __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, u
     else         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
-// Loader roles: wavefronts 0-3 stream the weight rows (8 pieces each per weight step),
-// wavefronts 4-7 the token rows (up to 5 pieces each per K-step).  The split matters because a
-// wavefront's loads complete in order: a single wavefront issuing both could not keep two weight
-// steps in flight while waiting for the much younger token step.
+// Loader roles: wavefronts 0-3 stream the weight rows (8 pieces each per K-step), wavefronts 4-7
+// the token rows (up to 10 pieces each per K-step, only those whose rows exist).  The two kinds go
+// out at different moments of a K-step (see k_loop), which one wavefront issuing both could not do
+// without making the token copies wait for the weight copies ahead of them: a wavefront's loads
+// complete in order.
 template <bool kStreamW>
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
@@ -156,26 +154,26 @@ __device__ __forceinline__ void wait_loads()
     __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// One K-step (32 k) of this wavefront: NTC token tiles x 2 weight tiles.  The 2 x NTC
-// (sub-step, token tile) pairs run as one software pipeline: the token operand of pair s+2 and
-// the weight operands of the next sub-step are requested from LDS before the MFMAs of pair s.
-template <int NTC>
-__device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws, const char *Xs, int half, f32x16 (&acc)[kWT][kTC])
+// One K-step (64 k) of this wavefront: NTC token tiles x 2 weight tiles x 4 sub-steps of 16 k.  The
+// (sub-step, token tile) pairs run as one software pipeline: the token operand of pair s+2 and the
+// weight operands of the next sub-step are requested from LDS before the MFMAs of pair s.  `mid` is
+// called once, half way through.
+template <int NTC, typename Mid>
+__device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws, const char *Xs, f32x16 (&acc)[kWT][kTC], Mid mid)
 {
     if constexpr (NTC > 0) {
         constexpr int KS = kBK / 16, STEPS = KS * NTC, D = 2;
         bf16x8 wf[2][kWT], xf[D + 1];
-        const uint32_t w0 = half ? c.woff[2] : c.woff[0], w1 = half ? c.woff[3] : c.woff[1];  // this half's two sub-steps
         auto fetch_w = [&](int ks) {
 #pragma unroll
             for (int a = 0; a < kWT; ++a) {
-                const uint4 v = *(const uint4 *)(Ws + (ks ? w1 : w0) + a * 32 * 128);
+                const uint4 v = *(const uint4 *)(Ws + c.woff[ks] + a * 32 * 128);
                 wf[ks & 1][a] = *(const bf16x8 *)&v;
             }
         };
         auto fetch_x = [&](int step) {
             const int ks = step / NTC, t = step % NTC;
-            const uint4 v = *(const uint4 *)(Xs + c.xoff[ks] + t * 64 * 64);
+            const uint4 v = *(const uint4 *)(Xs + c.xoff[ks] + t * 64 * 128);
             xf[step % (D + 1)] = *(const bf16x8 *)&v;
         };
         fetch_w(0);
@@ -184,6 +182,7 @@ __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws,
 #pragma unroll
         for (int step = 0; step < STEPS; ++step) {
             const int ks = step / NTC, t = step % NTC;
+            if (step == STEPS / 2) mid();
             if (t == 0 && ks + 1 < KS) fetch_w(ks + 1);
             if (step + D < STEPS) fetch_x(step + D);
 #pragma unroll
@@ -191,55 +190,29 @@ __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws,
                 acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], xf[step % (D + 1)], acc[a][t], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);  // keep the written order: the prefetch depth is the register budget
         }
+    } else {
+        mid();
     }
 }
 
 template <int NTC, bool kStreamW>
 __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int KT, f32x16 (&acc)[kWT][kTC])
 {
-    // KT K-steps of 32; weight steps cover two of them.  The caller issued weight steps 0, 1 and
-    // token steps 0, 1 (those that exist).  Weight step ws + 2 is issued at the end of the second
-    // K-step of weight step ws, into the slot of weight step ws - 1, which every wavefront left at
-    // the barrier before that K-step.
+    // KT K-steps of 64.  Both rings are two deep: step kt+1 is copied while step kt is multiplied.  The
+    // caller issued step 0.  Token copies go out right after the barrier, the weight copies half way
+    // through the multiply: a compute unit returns copies in issue order, and token copies (L2 hits)
+    // issued just behind a burst of weight copies would wait out that burst's HBM latency.
     const bool wloader = c.wave < 4;
     const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
-    const int WT_ = KT / 2;                                    // weight steps
-    int wslot = 0, xslot = 0, wfill = kNW - 1, xfill = kNX - 1;
+    int slot = 0;
     for (int kt = 0; kt < KT; ++kt) {
-        const int half = kt & 1, ws = kt >> 1;
-        // this wavefront's share of what step kt reads must have landed; younger steps stay in flight
-        if (wloader) {
-            if (!half) { if (ws + 1 < WT_) wait_loads<kWPieces>(); else wait_loads<0>(); }
-        } else {
-            if (kt + 1 < KT) {   // one younger token step (xlive loads) may stay in flight
-                switch (c.xlive) {
-                case 5: wait_loads<5>(); break;
-                case 4: wait_loads<4>(); break;
-                case 3: wait_loads<3>(); break;
-                case 2: wait_loads<2>(); break;
-                case 1: wait_loads<1>(); break;
-                default: wait_loads<0>(); break;
-                }
-            } else {
-                wait_loads<0>();
-            }
-        }
-        __syncthreads();  // everyone's share of step kt is in LDS; everyone is done reading step kt-1
-        if (!wloader && kt + kNX - 1 < KT) issue_step<kStreamW>(c, xring + xfill * kXStage, (kt + kNX - 1) * kBK);
-        multiply_stage<NTC>(c, ring + wslot * kWStage, ring + kNW * kWStage + xslot * kXStage, half, acc);
-        // The next weight step goes out AFTER the multiply of the second half of a weight step, not
-        // right after the barrier: the compute unit returns copies in the order they were issued, so
-        // token copies (L2 hits, needed two K-steps on) issued just behind a burst of weight copies
-        // wait out that burst's HBM latency.  Issued here -- the weight loaders reach the barrier
-        // early anyway -- the burst falls between two rounds of token copies, with most of a K-step
-        // to the next one (qwen3 GEMM-1 276 -> 265 us, GEMM-2 166 -> 156 us).
-        if (half) {
-            if (wloader && ws + kNW - 1 < WT_) issue_step<kStreamW>(c, wring + wfill * kWStage, (ws + kNW - 1) * kBKW);
-            wslot = wslot + 1 == kNW ? 0 : wslot + 1;
-            wfill = wfill + 1 == kNW ? 0 : wfill + 1;
-        }
-        xslot = xslot + 1 == kNX ? 0 : xslot + 1;
-        xfill = xfill + 1 == kNX ? 0 : xfill + 1;
+        wait_loads<0>();   // this wavefront's share of step kt has landed (nothing younger is in flight)
+        __syncthreads();   // everyone's share of step kt is in LDS; everyone is done reading step kt-1
+        const bool more = kt + 1 < KT;
+        if (!wloader && more) issue_step<kStreamW>(c, xring + (slot ^ 1) * kXStage, (kt + 1) * kBK);
+        multiply_stage<NTC>(c, ring + slot * kWStage, ring + kNW * kWStage + slot * kXStage, acc,
+                            [&]() { if (wloader && more) issue_step<kStreamW>(c, wring + (slot ^ 1) * kWStage, (kt + 1) * kBKW); });
+        slot ^= 1;
     }
 }
 
@@ -412,7 +385,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     c.wn = c.wave & 3;
     c.wm = c.wave >> 2;
     c.n_tt = (mt.rows + 31) >> 5;                      // token tiles that exist
-    c.xlive = c.wave < 4 ? 0 : min(kXPieces, max(0, (2 * c.n_tt - (c.wave & 3) + 3) >> 2));  // pieces w, w+4, ... < 2*n_tt
+    c.xlive = c.wave < 4 ? 0 : min(kXPieces, c.n_tt);  // pieces w, w+4, ... < 4*n_tt (8 rows each)
 
     // ---- staging plan ----
     // this workgroup's K range: everything, or (phase 1) weight steps [w0, w1) of the tile
@@ -443,10 +416,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     } else {
 #pragma unroll
         for (int i = 0; i < kXPieces; ++i) {
-            // token piece: rows [16*pc, 16*pc+16) of the token tile, 64 bytes each (rows past the chunk re-read its last row)
+            // token piece: rows [8*pc, 8*pc+8) of the token tile, 128 bytes each (rows past the chunk re-read its last row)
             const int pc = (c.wave & 3) + 4 * i;   // interleaved over the 4 loaders so that live pieces are shared evenly
-            const int row = pc * 16 + (c.lane >> 2);
-            const int chunk = (c.lane & 3) ^ swz(row);
+            const int row = pc * 8 + (c.lane >> 3);
+            const int chunk = (c.lane & 7) ^ swz8(row);
             const int r = min(row, mt.rows - 1);
             const int sr = kFirst ? p.perm[mt.row_begin + r] : mt.row_begin + r;
             c.off[i] = ((uint32_t)sr * K + chunk * 8) * 2;
@@ -458,14 +431,13 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
 #pragma unroll
         for (int ks = 0; ks < kBKW / 16; ++ks) c.woff[ks] = wr * 128 + (((ks * 2 + khalf) ^ swz8(wr)) << 4);
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) c.xoff[ks] = xr * 64 + (((ks * 2 + khalf) ^ swz(xr)) << 4);
+        for (int ks = 0; ks < kBK / 16; ++ks) c.xoff[ks] = xr * 128 + (((ks * 2 + khalf) ^ swz8(xr)) << 4);
     }
 
-    const int KT = (w1 - w0) * (kBKW / kBK);
+    const int KT = w1 - w0;
     if (kPhase != 2) {
         const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
-        if (c.wave < 4) { for (int s = 0; s < kNW - 1 && s < KT / 2; ++s) issue_step<!kFirst>(c, wring + s * kWStage, s * kBKW); }
-        else            { for (int s = 0; s < kNX - 1 && s < KT; ++s) issue_step<!kFirst>(c, xring + s * kXStage, s * kBK); }
+        if (KT > 0) issue_step<!kFirst>(c, c.wave < 4 ? wring : xring, 0);
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
