@@ -230,7 +230,7 @@ __device__ __forceinline__ float *partial_at(float *set, int wave, int a, int t,
 // measured and is slower: the device-wide fence it needs costs more than the third launch.)
 template <bool kFirst, int NTC, int kPhase>
 __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, int KT, char *ring,
-                                          float *tile_sets, int part, int n_parts)
+                                          float *tile_sets, int part, int n_parts, int tsel)
 {
     f32x16 acc[kWT][kTC];
 #pragma unroll
@@ -265,6 +265,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
                 for (int t = 0; t < NTC; ++t)
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) {
+                        if (t != tsel) continue;
                         const float4 v = *(const float4 *)partial_at(set, c.wave, a, t, r4, c.lane);
                         acc[a][t][r4 * 4] += v.x; acc[a][t][r4 * 4 + 1] += v.y; acc[a][t][r4 * 4 + 2] += v.z; acc[a][t][r4 * 4 + 3] += v.w;
                     }
@@ -283,6 +284,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
     const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
 #pragma unroll
     for (int t = 0; t < NTC; ++t) {
+        if (kPhase == 2 && t != tsel) continue;   // phase 2: one token tile per wavefront and workgroup
         char *row = mine + l31 * STRIDE;
 #pragma unroll
         for (int a = 0; a < kWT; ++a) {
@@ -441,14 +443,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
+    const int tsel = kPhase == 2 ? (int)blockIdx.y : -1;   // phase 2 is spread over the token tiles too: a workgroup adds up one per wavefront
     const int ntc = (c.n_tt - c.wm + 1) >> 1;
     switch (ntc) {
-    case 5: wave_body<kFirst, 5, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
-    case 4: wave_body<kFirst, 4, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
-    case 3: wave_body<kFirst, 3, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
-    case 2: wave_body<kFirst, 2, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
-    case 1: wave_body<kFirst, 1, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
-    default: wave_body<kFirst, 0, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts); break;
+    case 5: wave_body<kFirst, 5, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    case 4: wave_body<kFirst, 4, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    case 3: wave_body<kFirst, 3, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    case 2: wave_body<kFirst, 2, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    case 1: wave_body<kFirst, 1, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    default: wave_body<kFirst, 0, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
     }
 }
 
@@ -483,13 +486,13 @@ hipError_t launch_experts_mfma8(const Pass &p0, int which, hipStream_t st)
         hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 0>), dim3(grid), dim3(kThreads), 0, st, p);
         if (p.k_split) {
             hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 1>), dim3(round_blocks), dim3(kThreads), 0, st, p);
-            hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 2>), dim3(round_blocks / 2), dim3(kThreads), 0, st, p);
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 2>), dim3(round_blocks / 2, kTC), dim3(kThreads), 0, st, p);
         }
     } else {
         hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 0>), dim3(grid), dim3(kThreads), 0, st, p);
         if (p.k_split) {
             hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 1>), dim3(round_blocks), dim3(kThreads), 0, st, p);
-            hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 2>), dim3(round_blocks / 2), dim3(kThreads), 0, st, p);
+            hipLaunchKernelGGL((k_expert_gemm_mfma8<false, 2>), dim3(round_blocks / 2, kTC), dim3(kThreads), 0, st, p);
         }
     }
     return hipGetLastError();
