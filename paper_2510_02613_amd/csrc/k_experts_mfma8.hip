@@ -1,4 +1,4 @@
-// Large-tile grouped SwiGLU expert GEMMs for prefill-sized groups (bf16, K % 32 == 0).
+// Large-tile grouped SwiGLU expert GEMMs for prefill-sized groups (bf16, H and I multiples of 64).
 //
 // Same computation as the 4-wavefront kernels (the expert FFN of Sec. 2.1 of the
 // paper over slot-grouped rows, weights addressed by slot so that a re-placement of
@@ -12,7 +12,8 @@
 //    (also out of L2: a copy instruction that touches 16 half lines costs the issuing
 //    wavefront twice one that touches 8 whole lines).  Both operands therefore travel
 //    in steps of 64 k -- one full line per row: 32 KB of weight rows, up to 40 KB of
-//    token rows per step -- through a 2-deep ring each, with their own loader
+//    token rows per step -- through a 2-deep ring each (144 of the 160 KB of LDS: a
+//    third weight step does not fit beside two token steps), with their own loader
 //    wavefronts.  The weight step is issued half way through a K-step's multiply,
 //    between two rounds of token copies (see k_loop: a compute unit returns copies in
 //    issue order).
