@@ -46,11 +46,55 @@ def _random_case(i):
     return wl, emap, local
 
 
+def _random_large_case(i):
+    """Prefill-sized bf16 layers: long contractions (with and without a split last round), contraction
+    lengths that the large-tile kernels take and do not take, many rows per slot."""
+    g = np.random.Generator(np.random.PCG64(5000 + i))
+    pick = lambda xs: xs[int(g.integers(len(xs)))]
+    hidden = int(pick([512, 1024, 2048, 4096, 4160, 7168]))
+    inter = int(pick([64, 128, 192, 320, 384]))
+    gate = pick(["softmax", "sigmoid_group"])
+    if gate == "sigmoid_group":
+        n_group, per = int(pick([2, 4, 8])), int(pick([4, 8]))
+        n_experts = n_group * per
+        topk_group = int(g.integers(1, n_group + 1))
+        top_k = int(g.integers(2, min(8, topk_group * per) + 1))
+    else:
+        n_group, topk_group = 1, 1
+        n_experts = int(pick([8, 16, 24, 40, 64]))
+        top_k = int(g.integers(2, min(8, n_experts) + 1))
+    n_shared = int(pick([0, 0, 1, 2]))
+    n_local = int(g.integers(max(1, n_experts // 2), n_experts + 1))
+    spare = int(pick([0, 3]))
+    n_slots = n_local + n_shared + spare
+    tokens = int(pick([700, 1100, 1800, 2600, 3300]))
+    b = int(g.integers(0, tokens // 2))
+    e = int(g.integers(tokens // 2, tokens + 1))
+    wl = MoEWorkload(name=f"big{i}", tokens=tokens, hidden=hidden, inter=inter, n_experts=n_experts, top_k=top_k,
+                     n_slots=n_slots, n_local=n_local, act_dtype="bf16", router_dtype=pick(["f32", "bf16"]),
+                     gate=gate, n_group=n_group, topk_group=topk_group, renormalize=bool(g.integers(2)),
+                     routed_scale=float(pick([1.0, 2.5])), n_shared=n_shared, shared_range=(b, e) if n_shared else (0, 0),
+                     zipf_s=float(pick([0.0, 1.2])), seed=6000 + i)
+    local = np.sort(g.choice(n_experts, size=n_local, replace=False))
+    slots = g.permutation(n_local + spare)[:n_local]
+    emap = np.full(n_experts, -1, np.int32)
+    emap[local] = slots
+    return wl, emap, local
+
+
 @pytest.mark.parametrize("i", range(24))
 def test_random_shape(i):
+    _check(*_random_case(i))
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_large_shape(i):
+    _check(*_random_large_case(i))
+
+
+def _check(wl, emap, local):
     from gpu_util import Case, check_routing, check_bookkeeping, check_output
     from workloads import make_inputs
-    wl, emap, local = _random_case(i)
     # the generator draws weights for logical experts 0..n_local-1 (+ shared); hand expert local[j] the j-th set
     inp = make_inputs(wl)
     case = Case.__new__(Case)
