@@ -461,7 +461,14 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
 int mfma8_tile_rows() { return kBM; }
 
 // usable when both contraction lengths are whole K-steps (direct-to-LDS loads cannot zero fill)
-bool mfma8_supports(const Pass &p) { return p.act_bf16 && p.H % kBKW == 0 && p.I % kBKW == 0; }
+// Whole K-steps only (the copies cannot zero fill), and the copies address their rows with 32-bit byte
+// offsets from the matrix base: x by token index, h by grouped row, a slot's weights by weight row.
+bool mfma8_supports(const Pass &p)
+{
+    const size_t lim = (size_t)1 << 32;
+    return p.act_bf16 && p.H % kBKW == 0 && p.I % kBKW == 0 &&
+           (size_t)p.T * p.H * 2 < lim && (size_t)p.T * p.kk * p.I * 2 < lim && (size_t)2 * p.I * p.H * 2 < lim;
+}
 
 size_t mfma8_partial_bytes() { return (size_t)kMaxPartialSets * kPartialFloats * sizeof(float); }
 
