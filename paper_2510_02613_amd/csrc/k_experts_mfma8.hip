@@ -85,6 +85,7 @@ struct WaveCtx {
     uint32_t off[kXPieces > kWPieces ? kXPieces : kWPieces];               // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
     uint32_t woff[kBKW / 16], xoff[kBK / 16]; // LDS byte offsets (inside a stage) of this lane's operand rows per sub-step
     int wave, lane, wm, wn, n_tt;
+    bool stream_w;                        // this tile's weight rows are read by no other tile: copy them non-temporally
     int xlive;                            // token-loader wavefronts: how many of their pieces hold rows that exist
 };
 
@@ -105,9 +106,11 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
 // Issued as inline assembly on purpose: the compiler's wait-count insertion would otherwise
 // hold every later LDS read until these loads (which belong to a LATER stage) have returned.
 // Completion is awaited explicitly (wait_loads) before the step's barrier.
-// kStream: the line is marked non-temporal -- read once and not worth a place in L2.  Used for the weights
-// of the second GEMM: the rows y it writes are read back by the combine kernel right after, and
-// stay in cache when the weight stream does not push them out.
+// kStream: the line is marked non-temporal -- read once and not worth a place in L2.  Used for the weight
+// rows of a slot whose rows are a single chunk (no other tile reads them): the weight stream then does not
+// push out what is read again -- the chunk's token rows (once per N-slice), h between the two GEMMs, and the
+// rows y that the combine kernel reads back right after.  A slot with several chunks keeps the default
+// policy, so that the later chunks find the weights in L2.
 template <bool kStream>
 __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, uint32_t lds_byte_addr)
 {
@@ -120,13 +123,17 @@ __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, u
 // out at different moments of a K-step (see k_loop), which one wavefront issuing both could not do
 // without making the token copies wait for the weight copies ahead of them: a wavefront's loads
 // complete in order.
-template <bool kStreamW>
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
     if (c.wave < 4) {
         const uint16_t *b = c.wbase + k0;
+        if (c.stream_w) {
 #pragma unroll
-        for (int i = 0; i < kWPieces; ++i) dma_piece<kStreamW>(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
+            for (int i = 0; i < kWPieces; ++i) dma_piece<true>(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kWPieces; ++i) dma_piece<false>(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
+        }
     } else {
         const uint16_t *b = c.abase + k0;
 #pragma unroll
@@ -196,7 +203,7 @@ __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws,
     }
 }
 
-template <int NTC, bool kStreamW>
+template <int NTC>
 __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int KT, f32x16 (&acc)[kWT][kTC])
 {
     // KT K-steps of 64.  Both rings are two deep: step kt+1 is copied while step kt is multiplied.  The
@@ -210,9 +217,9 @@ __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int K
         wait_loads<0>();   // this wavefront's share of step kt has landed (nothing younger is in flight)
         __syncthreads();   // everyone's share of step kt is in LDS; everyone is done reading step kt-1
         const bool more = kt + 1 < KT;
-        if (!wloader && more) issue_step<kStreamW>(c, xring + (slot ^ 1) * kXStage, (kt + 1) * kBK);
+        if (!wloader && more) issue_step(c, xring + (slot ^ 1) * kXStage, (kt + 1) * kBK);
         multiply_stage<NTC>(c, ring + slot * kWStage, ring + kNW * kWStage + slot * kXStage, acc,
-                            [&]() { if (wloader && more) issue_step<kStreamW>(c, wring + (slot ^ 1) * kWStage, (kt + 1) * kBKW); });
+                            [&]() { if (wloader && more) issue_step(c, wring + (slot ^ 1) * kWStage, (kt + 1) * kBKW); });
         slot ^= 1;
     }
 }
@@ -241,7 +248,7 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
     if (kPhase != 2) {
-        k_loop<NTC, !kFirst>(c, ring, KT, acc);
+        k_loop<NTC>(c, ring, KT, acc);
         __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
     }
     if (kPhase == 1) {
@@ -388,6 +395,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     c.wn = c.wave & 3;
     c.wm = c.wave >> 2;
     c.n_tt = (mt.rows + 31) >> 5;                      // token tiles that exist
+    c.stream_w = p.counts[mt.slot] <= kBM;             // the slot's rows are one chunk: nobody else reads these weights
     c.xlive = c.wave < 4 ? 0 : min(kXPieces, c.n_tt);  // pieces w, w+4, ... < 4*n_tt (8 rows each)
 
     // ---- staging plan ----
@@ -440,7 +448,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     const int KT = w1 - w0;
     if (kPhase != 2) {
         const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
-        if (KT > 0) issue_step<!kFirst>(c, c.wave < 4 ? wring : xring, 0);
+        if (KT > 0) issue_step(c, c.wave < 4 ? wring : xring, 0);
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
