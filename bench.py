@@ -33,8 +33,8 @@ PEAK_HBM_GBS = 8000.0
 # WRITE_SIZE, scaled by the factor a plain copy of known size gives): bytes, or None when no
 # counter run has been recorded for that workload.  The summaries sit under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/grouped_gemm1_qwen3_30b_a3b.md: FETCH_SIZE 457603.0 KiB x 2.000 + WRITE_SIZE 49152.0 KiB x 1.000
-    "qwen3_30b_a3b": int((457603.0 * 2.0 + 49152.0) * 1024),
+    # profiles/grouped_gemm1_qwen3_30b_a3b.md: FETCH_SIZE 457507.7 KiB x 2.000 + WRITE_SIZE 49152.0 KiB x 1.000
+    "qwen3_30b_a3b": int((457507.7 * 2.0 + 49152.0) * 1024),
     # profiles/grouped_gemm1_dsv3_ep8_decode.md: FETCH_SIZE 810836.2 KiB x 2.000 + WRITE_SIZE 232.0 KiB x 1.000
     "dsv3_ep8_decode": int((810836.2 * 2.0 + 232.0) * 1024),
     # profiles/grouped_gemm1_dsv3_ep8_rank.md: the three GEMM-1 launches of a pass together,
