@@ -38,8 +38,8 @@ MEASURED_TRAFFIC_BYTES = {
     # profiles/grouped_gemm1_dsv3_ep8_decode.md: FETCH_SIZE 810836.2 KiB x 2.000 + WRITE_SIZE 232.0 KiB x 1.000
     "dsv3_ep8_decode": int((810836.2 * 2.0 + 232.0) * 1024),
     # profiles/grouped_gemm1_dsv3_ep8_rank.md: the three GEMM-1 launches of a pass together,
-    # FETCH_SIZE (1024757.4 + 128526.6 + 31864.8) KiB x 2.000 + WRITE_SIZE (32376.0 + 63488.0 + 3920.0) KiB x 1.000
-    "dsv3_ep8_rank": int(((1024757.4 + 128526.6 + 31864.8) * 2.0 + 32376.0 + 63488.0 + 3920.0) * 1024),
+    # FETCH_SIZE (1024518.9 + 128533.2 + 31854.8) KiB x 2.000 + WRITE_SIZE (32376.0 + 63488.0 + 3920.0) KiB x 1.000
+    "dsv3_ep8_rank": int(((1024518.9 + 128533.2 + 31854.8) * 2.0 + 32376.0 + 63488.0 + 3920.0) * 1024),
 }
 
 
