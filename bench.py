@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE rank layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|NAME]
 
 A step is one whole forward pass of the layer (gate, permute, both grouped expert
 GEMMs, combine) over one batch of synthetic tokens that is already resident in
-HBM.  Prints ONE JSON line: whole-layer tokens/s, the roofline position of the
-dominant kernel (timed with HIP events on the pass's own stream, inside the timed
-region) and the fp64 CPU oracle timed on a bounded token sample of the same
-workload on this machine's host cores.
+HBM.  By default all five benchmark configurations run, one after the other, in
+this process; the headline (`value`, `config.workload`, `roofline`,
+`cpu_baseline`) is the largest one, the DeepSeek-V3-shaped rank, and `workloads`
+carries the same figures for every configuration: step time, tokens/s, per-kernel
+times, the roofline position of the dominant kernel (timed with HIP events on the
+pass's own stream, inside the timed region) and of the whole layer -- against the
+bf16 MFMA peak for the prefill-sized batches, against the HBM peak for the
+decode-sized one -- and, for the re-layout configuration, both phases, the
+slot-order placement and what the switches did to device memory.  The fp64 CPU
+oracle is timed on a bounded token sample of the headline workload on this machine's
+host cores.  Prints ONE JSON line.
 
 Only one GPU is used: the layer is one expert-parallel rank's share of the work.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -28,28 +36,74 @@ sys.path.insert(0, ROOT)
 # published MI355X peaks
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+PEAK_F32_VALU_TFLOPS = 157.3
 
-# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc runs (FETCH_SIZE and
-# WRITE_SIZE, scaled by the factor a plain copy of known size gives): bytes, or None when no
-# counter run has been recorded for that workload.  The summaries sit under profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/grouped_gemm1_qwen3_30b_a3b.md: FETCH_SIZE 457507.7 KiB x 2.000 + WRITE_SIZE 49152.0 KiB x 1.000
-    "qwen3_30b_a3b": int((457507.7 * 2.0 + 49152.0) * 1024),
-    # profiles/grouped_gemm1_dsv3_ep8_decode.md: FETCH_SIZE 810836.2 KiB x 2.000 + WRITE_SIZE 232.0 KiB x 1.000
-    "dsv3_ep8_decode": int((810836.2 * 2.0 + 232.0) * 1024),
-    # profiles/grouped_gemm1_dsv3_ep8_rank.md: the three GEMM-1 launches of a pass together,
-    # FETCH_SIZE (1024518.9 + 128533.2 + 31854.8) KiB x 2.000 + WRITE_SIZE (32376.0 + 63488.0 + 3920.0) KiB x 1.000
-    "dsv3_ep8_rank": int(((1024518.9 + 128533.2 + 31854.8) * 2.0 + 32376.0 + 63488.0 + 3920.0) * 1024),
-}
+# the five benchmark configurations, headline first
+HEADLINE = "dsv3_ep8_rank"
+ALL_WORKLOADS = ("dsv3_ep8_rank", "qwen3_30b_a3b", "dsv3_ep8_decode", "qwen3_relayout", "tiny_f32")
+
+# HBM traffic of the dominant kernel per launch, measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
+# each scaled by what the same counter reads for a plain copy of known size).  The record names the
+# kernel and carries a hash of the sources it was taken on: when those have changed since, the figure
+# is stale and `traffic` is null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def source_hash(paths):
+    h = hashlib.sha256()
+    for rel in sorted(paths):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(rel.encode() + b"\0" + f.read() + b"\0")
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """Bytes per launch of the dominant kernel from profiles/traffic.json, or None when there is no record
+    for this workload or the kernel's sources have changed since it was taken."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(workload)
+        if not rec or source_hash(rec["sources"]) != rec["source_sha256"]:
+            return None
+        return int(rec["bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def record_traffic(args):
+    """--record-traffic WORKLOAD FETCH_KIB WRITE_KIB FETCH_SCALE WRITE_SCALE: store the counter figures of a
+    rocprofv3 --pmc run (KiB per launch of the dominant kernel, summed over its launches of one pass) with
+    the hash of the kernel sources as they are now."""
+    name, fetch_kib, write_kib, fs, ws_ = args.record_traffic
+    sources = sorted(os.path.join("paper_2510_02613_amd", "csrc", f)
+                     for f in os.listdir(os.path.join(ROOT, "paper_2510_02613_amd", "csrc"))
+                     if f.startswith("k_experts") or f in ("moe_internal.h", "k_permute.hip"))
+    try:
+        with open(TRAFFIC_FILE) as f:
+            allrec = json.load(f)
+    except OSError:
+        allrec = {}
+    allrec[name] = {
+        "kernel": args.traffic_kernel, "profile": args.traffic_profile,
+        "fetch_size_kib": float(fetch_kib), "write_size_kib": float(write_kib),
+        "fetch_scale": float(fs), "write_scale": float(ws_),
+        "bytes_per_launch": int((float(fetch_kib) * float(fs) + float(write_kib) * float(ws_)) * 1024),
+        "sources": sources, "source_sha256": source_hash(sources),
+    }
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(allrec, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print(json.dumps(allrec[name]))
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="qwen3_30b_a3b",
-                    help="qwen3_30b_a3b (headline) | dsv3_ep8_rank | dsv3_ep8_decode | qwen3_relayout | dsv2_lite | tiny_f32")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all (the five configurations, headline dsv3_ep8_rank) | dsv3_ep8_rank | qwen3_30b_a3b | "
+                         "dsv3_ep8_decode | qwen3_relayout | tiny_f32 | dsv2_lite")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel events inside the timed region (roofline then is null)")
@@ -70,6 +124,10 @@ def parse_args():
                     help="skip the two measuring-stick kernels (sustained MFMA rate, streaming read) after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (counter calibration for rocprofv3 --pmc) and exit")
+    ap.add_argument("--record-traffic", nargs=5, metavar=("WORKLOAD", "FETCH_KIB", "WRITE_KIB", "FETCH_SCALE", "WRITE_SCALE"),
+                    help="no GPU work: store counter figures of a rocprofv3 --pmc run in profiles/traffic.json")
+    ap.add_argument("--traffic-kernel", default="grouped GEMM-1 + SwiGLU", help="with --record-traffic: kernel symbol(s) the figures are for")
+    ap.add_argument("--traffic-profile", default="", help="with --record-traffic: the profiles/ summary that holds the command and the raw figures")
     return ap.parse_args()
 
 
@@ -97,34 +155,14 @@ def algorithmic_work(wl, counts, shared_rows):
     }
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs one expert-parallel rank on ONE GPU; --gpus must be 1 "
-              "(no collectives or sharding are part of it)", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    dev = torch.device("cuda:0")
-
-    if args.copy_calibration:
-        n = 1 << 30
-        src = torch.empty(n, dtype=torch.uint8, device=dev).zero_()
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_each_way": n, "launches": 5}))
-        return
-
+def run_workload(torch, args, name, extras=False):
+    """Builds the layer of one configuration on the GPU, times args.steps passes after args.warmup, and
+    returns (figures for the JSON line, state for the optional legs that follow)."""
     from workloads import get_workload, make_inputs, relayout_maps, block_expert_map, shared_slots_of, build_slot_pool
     from paper_2510_02613_amd import binding as B
     from paper_2510_02613_amd.layer import MoELayer
-
-    wl = get_workload(args.workload)
+    dev = torch.device("cuda:0")
+    wl = get_workload(name)
     inp = make_inputs(wl, threads=16)
     if wl.name == "qwen3_relayout":
         expert_map = relayout_maps(wl)[1]
@@ -183,6 +221,7 @@ def main():
         torch.cuda.synchronize()
         B.moe_profile_enable(layer.handle, every)
 
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -203,76 +242,135 @@ def main():
     counts = view["counts"]
     work = algorithmic_work(wl, counts, wl.shared_range[1] - wl.shared_range[0])
     decode = wl.name == "dsv3_ep8_decode"
+    t_step = ms_per_step * 1e-3
+
+    # whole layer against both roofs; the one the metric names for this batch size is `bound`
+    layer_fig = {"bound": "hbm" if decode else "mfma",
+                 "tflops": work["flops_total"] / t_step / 1e12,
+                 "frac_bf16_mfma_peak": work["flops_total"] / t_step / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+                 "min_hbm_gbs": work["bytes_layer_min"] / t_step / 1e9,
+                 "frac_hbm_peak": work["bytes_layer_min"] / t_step / 1e9 / PEAK_HBM_GBS,
+                 "phase_us": {k: v * 1e3 for k, v in phases.items()} if phases else None}
+    if wl.act_dtype != "bf16":
+        layer_fig["bound"] = "launch latency (fp32 parity configuration: 6 MFLOP per pass)"
 
     roofline = None
-    if phases:
+    if phases and wl.act_dtype == "bf16":
         dom = "gemm1"
         t_dom = phases[dom] * 1e-3
-        if decode:
-            ach = work["bytes_gemm1"] / t_dom / 1e9
-            roofline = {"bound": "hbm", "kernel": "grouped GEMM-1 + SwiGLU", "achieved": ach, "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
-        else:
-            ach = work["flops_gemm1"] / t_dom / 1e12
-            roofline = {"bound": "mfma", "kernel": "grouped GEMM-1 + SwiGLU", "achieved": ach,
-                        "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_MFMA_TFLOPS}
-            # the same launch against the other roof: with ~256 rows per expert the kernel sits below the
-            # ridge (flops per algorithmic byte < 2500/8), so HBM is the tighter of the two
-            gbs = work["bytes_gemm1"] / t_dom / 1e9
-            roofline["other_roof"] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                      "frac": gbs / PEAK_HBM_GBS,
-                                      "flop_per_byte": work["flops_gemm1"] / work["bytes_gemm1"],
-                                      "ridge_flop_per_byte": PEAK_BF16_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS}
-        roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(wl.name)
+        gbs = work["bytes_gemm1"] / t_dom / 1e9
+        tfl = work["flops_gemm1"] / t_dom / 1e12
+        hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+        mfma = {"bound": "mfma", "achieved": tfl, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tfl / PEAK_BF16_MFMA_TFLOPS}
+        roofline = dict(hbm if decode else mfma)
+        roofline["kernel"] = "grouped GEMM-1 + SwiGLU"
+        # the same launch against the other roof: with ~256 rows per expert the prefill kernel sits below the
+        # ridge (flops per algorithmic byte < 2500/8), so HBM is the tighter of its two roofs
+        roofline["other_roof"] = dict(mfma if decode else hbm, flop_per_byte=work["flops_gemm1"] / work["bytes_gemm1"],
+                                      ridge_flop_per_byte=PEAK_BF16_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS)
+        roofline["traffic"] = measured_traffic(wl.name)
         roofline["avg_launch_us"] = phases[dom] * 1e3
         roofline["algorithmic_per_launch"] = work["bytes_gemm1"] if decode else work["flops_gemm1"]
+        roofline["layer_frac"] = layer_fig["frac_hbm_peak"] if decode else layer_fig["frac_bf16_mfma_peak"]
 
-    result = {
-        "metric": "MoE layer tokens/s at 1 MI355X; % bf16 MFMA peak (prefill), % HBM BW (decode)",
-        "value": wl.tokens / (ms_per_step * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.act_dtype, "data": "synthetic",
+    fig = {
+        "ms_per_step": ms_per_step, "tokens_per_s": wl.tokens / t_step, "dtype": wl.act_dtype,
         "config": {"workload": wl.name, "weight_pools": "virtual (moe_vpool)" if args.virtual_pool else "plain",
                    "launch": "hip graph replay" if args.hip_graph else "eager", "tokens": wl.tokens, "hidden": wl.hidden, "inter": wl.inter,
                    "n_experts": wl.n_experts, "top_k": wl.top_k, "local_slots": int((expert_map >= 0).sum()) + wl.n_shared,
                    "gate": wl.gate, "assignments": work["assignments"], "active_slots": work["active_slots"],
                    "rows_per_slot_max": int(counts.max()), "rows_per_slot_mean": float(counts[counts > 0].mean()) if (counts > 0).any() else 0.0},
-        "layer": {"tflops": work["flops_total"] / (ms_per_step * 1e-3) / 1e12,
-                  "frac_bf16_mfma_peak": work["flops_total"] / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
-                  "min_hbm_gbs": work["bytes_layer_min"] / (ms_per_step * 1e-3) / 1e9,
-                  "frac_hbm_peak": work["bytes_layer_min"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                  "phase_us": {k: v * 1e3 for k, v in phases.items()} if phases else None},
-        "roofline": roofline,
+        "layer": layer_fig, "roofline": roofline,
     }
-
-    if args.scale_while_serve is not None:
-        if wl.name != "qwen3_relayout":
-            print("bench.py: --scale-while-serve needs --workload qwen3_relayout", file=sys.stderr)
-            sys.exit(2)
-        result["scale_while_serve"] = scale_while_serve(torch, layer, wl, inp, x, out, stream, args)
-
+    state = dict(wl=wl, inp=inp, layer=layer, x=x, out=out, stream=stream, w13_pool=w13_pool, w2_pool=w2_pool,
+                 expert_map=expert_map, shared=shared, pools=pools)
     if wl.name == "qwen3_relayout":
-        result["relayout"] = relayout_report(torch, layer, wl, inp, x, out, stream, w13_pool, w2_pool)
+        fig["relayout"] = relayout_report(torch, layer, wl, inp, x, out, stream, w13_pool, w2_pool)
+    return fig, state
 
-    if args.replicate_hot is not None:
-        if wl.name != "qwen3_relayout" or not 0 < args.replicate_hot <= wl.n_slots // 2:
-            print("bench.py: --replicate-hot N needs --workload qwen3_relayout and 0 < N <= %d" % (wl.n_slots // 2), file=sys.stderr)
-            sys.exit(2)
-        result["replicate_hot"] = replicate_hot(torch, layer, wl, x, out, stream, args.replicate_hot)
 
-    if not args.no_ceilings:
-        result["ceilings"] = measure_ceilings(torch, B, layer, stream)
+def release(torch, state):
+    torch.cuda.synchronize()
+    state["layer"].close()
+    for pool in state["pools"].values():
+        pool.close()
+    state.clear()
+    torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, args.cpu_seconds)
-    print(json.dumps(result))
-    if pools:
+
+def main():
+    args = parse_args()
+    if args.record_traffic:
+        record_traffic(args)
+        return
+    if args.gpus != 1:
+        print("bench.py: this build runs one expert-parallel rank on ONE GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).zero_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
         torch.cuda.synchronize()
-        layer.close()
-        for pool in pools.values():
-            pool.close()
+        print(json.dumps({"copy_bytes_each_way": n, "launches": 5}))
+        return
+
+    from paper_2510_02613_amd import binding as B
+    names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
+    single = len(names) == 1
+    for flag, val in (("--scale-while-serve", args.scale_while_serve), ("--replicate-hot", args.replicate_hot)):
+        if val is not None and names != ("qwen3_relayout",):
+            print(f"bench.py: {flag} needs --workload qwen3_relayout", file=sys.stderr)
+            sys.exit(2)
+
+    head_fig, extras, per_workload = None, {}, {}
+    for i, name in enumerate(names):
+        t_wall = time.perf_counter()
+        fig, state = run_workload(torch, args, name)
+        if i == 0:
+            head_fig = fig
+            wl = state["wl"]
+            if args.scale_while_serve is not None:
+                extras["scale_while_serve"] = scale_while_serve(torch, state["layer"], wl, state["inp"], state["x"], state["out"], state["stream"], args)
+            if args.replicate_hot is not None:
+                if not 0 < args.replicate_hot <= wl.n_slots // 2:
+                    print("bench.py: --replicate-hot N needs 0 < N <= %d" % (wl.n_slots // 2), file=sys.stderr)
+                    sys.exit(2)
+                extras["replicate_hot"] = replicate_hot(torch, state["layer"], wl, state["x"], state["out"], state["stream"], args.replicate_hot)
+            if not args.no_ceilings:
+                extras["ceilings"] = measure_ceilings(torch, B, state["layer"], state["stream"])
+            if not args.no_cpu_baseline:
+                extras["cpu_baseline"] = cpu_baseline(wl, state["inp"], state["w13_pool"], state["w2_pool"], state["expert_map"],
+                                                      state["shared"], args.cpu_seconds)
+        fig["wall_s"] = time.perf_counter() - t_wall
+        per_workload[name] = fig
+        print(f"bench.py: {name}: {fig['ms_per_step'] * 1e3:.1f} us/step", file=sys.stderr, flush=True)
+        release(torch, state)
+
+    result = {
+        "metric": "MoE layer tokens/s at 1 MI355X; % bf16 MFMA peak (prefill), % HBM BW (decode)",
+        "value": head_fig["tokens_per_s"],
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head_fig["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head_fig["dtype"], "data": "synthetic",
+        "config": head_fig["config"], "layer": head_fig["layer"], "roofline": head_fig["roofline"],
+    }
+    if "relayout" in head_fig:
+        result["relayout"] = head_fig["relayout"]
+    result.update(extras)
+    if not single:
+        result["workloads"] = {n: {k: v for k, v in f.items() if k != "dtype"} for n, f in per_workload.items()}
+    print(json.dumps(result))
 
 
 def scale_while_serve(torch, layer, wl, inp, x, out, stream, args):

@@ -92,8 +92,12 @@ typedef struct {
 
 typedef struct {
     const void  *router_w;    /* device [E,H] row-major, router_dtype */
-    const float *logit_bias;  /* device [E] fp32 or NULL; added to the logits before scoring */
-    const float *select_bias; /* device [E] fp32 or NULL; added to scores for SELECTION only */
+    const float *logit_bias;  /* device [E] fp32 or NULL; added to the logits before scoring; finite values */
+    const float *select_bias; /* device [E] fp32 or NULL; added to scores for SELECTION only; finite values.
+                               * (With non-finite biases or activations a token may be left with fewer than k
+                               * candidates: its selection is then unspecified -- ids stay inside [0, E), an id
+                               * may repeat, and a repeated id carries weight 0 -- and nothing is read or written
+                               * out of bounds.) */
     const void  *w13;         /* device [S,2I,H] act_dtype: rows 0..I-1 gate proj, I..2I-1 up proj */
     const void  *w2;          /* device [S,H,I]  act_dtype: down proj */
     void        *workspace;   /* device, 256-byte aligned, >= moe_workspace_bytes(cfg) bytes */
@@ -145,11 +149,16 @@ moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf,
  *   host_shared_slots [n_shared]  slots of the shared experts (NULL iff n_shared == 0).
  * Rejected with MOE_ERR_MAP, leaving the old map active: n != E, an entry < -1 or
  * >= S, two experts (or an expert and a shared expert) on one slot.
- * The table is copied out of the host arrays before the call returns.  The device
- * copy is written by a tiny kernel enqueued on `hip_stream` into the INACTIVE one
- * of two device tables; forwards enqueued earlier keep reading the old table, and
- * forwards issued after this call read the new one.  No allocation, no
- * synchronisation, no weight traffic.  The caller must have filled the newly
+ * The table is copied out of the host arrays before the call returns.  The layer has
+ * ONE device table at a fixed address in the workspace, rewritten in place by a tiny
+ * kernel enqueued on `hip_stream`: passes enqueued on that stream before this call have
+ * read the old table by then (the old placement stays in force for them), passes
+ * enqueued after it read the new one -- a replay of a HIP graph captured earlier
+ * included, since a captured pass holds nothing of the placement but the table's
+ * address.  Passes that run on OTHER streams are the caller's to order against the
+ * switch (a pass that overlaps the rewrite could read a mixture of the two
+ * placements).  No allocation, no synchronisation, no weight traffic.  The caller
+ * must have filled the newly
  * referenced weight slots (stream-ordered before the next forward).
  */
 moe_status_t moe_set_expert_map(moe_layer_t *layer, const int32_t *host_map, int32_t n,
@@ -170,7 +179,7 @@ moe_status_t moe_set_expert_map(moe_layer_t *layer, const int32_t *host_map, int
  * the same weights for the layer to compute the same function (not checked).
  * Rejected with MOE_ERR_MAP, leaving the old placement active: n != E, offsets that do not
  * start at 0, decrease or exceed S, a slot outside [0, S), a slot used twice.
- * Everything else -- the two device tables, ordering on `hip_stream`, no allocation, no
+ * Everything else -- the one device table, ordering on `hip_stream`, no allocation, no
  * weight traffic, the wait for pending slot fills -- as in moe_set_expert_map, which is
  * the case of at most one copy per expert.
  */

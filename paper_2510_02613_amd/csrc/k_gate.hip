@@ -166,6 +166,7 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
     // top-k by repeated wavefront arg-max
     int my_id = 0;
     float my_s = 0.f;
+    bool none = false;         // this lane's selection round found no candidate
     constexpr int kRegs = 8;   // up to 512 experts: the candidates live in registers, entry i of a lane is expert lane + 64 i
     if (E <= 64 * kRegs) {
         // NR = registers in use; the winners' scores are fetched once, after the last round.
@@ -196,7 +197,9 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
                     win = wave_min_i32(best == m && m != 0u ? lane + 64 * bi : 0x7fffffff);
                     if (win == 0x7fffffff) win = -1;             // no candidate left
                 }
-                if (lane == j) my_id = win;
+                // fewer than k candidates (non-finite biases or activations): the slot keeps id 0 with
+                // weight 0 (my_s is only fetched for a real winner), so that nothing is indexed by -1
+                if (lane == j) { my_id = win < 0 ? 0 : win; none = win < 0; }
 #pragma unroll
                 for (int i = 0; i < NR; ++i)
                     if (lane + 64 * i == win) c[i] = 0u;
@@ -205,7 +208,7 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
         if (E <= 128)      rounds(std::integral_constant<int, 2>{});
         else if (E <= 256) rounds(std::integral_constant<int, 4>{});
         else               rounds(std::integral_constant<int, kRegs>{});
-        if (lane < p.k) my_s = lg[my_id];
+        if (lane < p.k) my_s = none ? 0.f : lg[my_id];
     } else {
         for (int j = 0; j < p.k; ++j) {
             unsigned long long key = 0ull;
@@ -214,6 +217,7 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
                 if (v != NEG) { unsigned long long kk = make_key(v, e); key = kk > key ? kk : key; }
             }
             key = wave_max_u64(key);
+            if (key == 0ull) continue;                     // no candidate left: id 0, weight 0 (wave-uniform)
             int win = key_index(key);
             if (lane == j) { my_id = win; my_s = lg[win]; }
             if (lane == (win & 63)) cs[win] = NEG;

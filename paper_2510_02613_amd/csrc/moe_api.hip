@@ -45,7 +45,7 @@ constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: siz
 
 // Offsets of every intermediate inside the workspace.
 struct Layout {
-    size_t map[2], logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
+    size_t map, logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
     bool has_partials;
 };
 
@@ -91,8 +91,7 @@ Layout make_layout(const moe_config_t &c)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     // a table: E + n_shared entries, then the copy lists of replicated experts (count, slots...:
     // at most S slots in lists of at least two, so 3S/2 entries)
-    L.map[0] = take(4 * (c.n_experts + c.n_shared + 2 * S));
-    L.map[1] = take(4 * (c.n_experts + c.n_shared + 2 * S));
+    L.map = take(4 * (c.n_experts + c.n_shared + 2 * S));
     L.logits = take(c.act_dtype == MOE_BF16 ? 4 * T * c.n_experts * kGatePlanes : 0);   // partial-sum planes of the K-split logits kernels
     L.ids = take(4 * T * k);
     L.w = take(4 * T * k);
@@ -129,7 +128,6 @@ struct moe_layer {
     moe_config_t cfg;
     moe_buffers_t buf;
     Layout lay;
-    int active;      // which of the two device tables forwards read
     bool has_map;
     std::vector<int32_t> slot_owner;  // per slot: entry (expert, or E + shared expert) of the active table that uses it, or -1
     // slot fills that the next map switch has to wait for (one event per fill, reused after the switch)
@@ -170,7 +168,6 @@ moe_status_t moe_layer_create(const moe_config_t *cfg, const moe_buffers_t *buf,
     l->cfg = *cfg;
     l->buf = *buf;
     l->lay = L;
-    l->active = 0;
     l->has_map = false;
     *out = l;
     return MOE_OK;
@@ -256,11 +253,12 @@ moe_status_t moe_profile_read(moe_layer_t *l, int32_t back, float *ms)
 
 namespace {
 
-// Validated placement -> the inactive device table, then make it the active one.
+// Validated placement -> the device table.  There is ONE table at a fixed address, rewritten in place by a
+// kernel on hip_stream: passes enqueued on that stream before the switch have read it by then, passes after it
+// (a replay of a captured graph included: the table's address is all a captured pass holds) read the new one.
 moe_status_t install_table(moe_layer_t *l, std::vector<int32_t> &table, std::vector<int32_t> &owner, void *hip_stream)
 {
-    const int target = l->has_map ? 1 - l->active : 0;
-    int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map[target]);
+    int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map);
     hipError_t e = hipSuccess;
     // slot fills enqueued by moe_load_expert: everything after this switch on hip_stream sees them complete
     for (int i = 0; i < l->n_pending && e == hipSuccess; ++i) e = hipStreamWaitEvent((hipStream_t)hip_stream, l->load_ev[i], 0);
@@ -268,7 +266,6 @@ moe_status_t install_table(moe_layer_t *l, std::vector<int32_t> &table, std::vec
     l->n_pending = 0;
     e = launch_write_map(dst, table.data(), (int)table.size(), (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
-    l->active = target;
     l->has_map = true;
     l->slot_owner.swap(owner);
     return MOE_OK;
@@ -288,17 +285,16 @@ moe_status_t claim_slot(const moe_config_t &c, std::vector<int32_t> &owner, int3
 
 }  // namespace
 
-moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t n,
-                                const int32_t *host_shared_slots, void *hip_stream)
+// Checks a plain placement (at most one slot per expert) and writes its device table (E + n_shared
+// entries) and the slot -> entry index (S entries) into caller-provided arrays.
+static moe_status_t validate_plain_map(const moe_config_t &c, const int32_t *host_map, int32_t n, const int32_t *host_shared_slots,
+                                       int32_t *table, int32_t *owner)
 {
-    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
     if (!host_map) return fail(MOE_ERR_ARG, "host_map is NULL");
-    const moe_config_t &c = l->cfg;
     if (n != c.n_experts) return fail(MOE_ERR_MAP, "map has %d entries, layer has %d logical experts", n, c.n_experts);
     if ((c.n_shared > 0) != (host_shared_slots != nullptr))
         return fail(MOE_ERR_MAP, "host_shared_slots must be given exactly when n_shared > 0");
-    std::vector<int32_t> owner(c.n_slots, -1);  // slot -> entry index that claimed it
-    std::vector<int32_t> table(c.n_experts + c.n_shared);
+    for (int s = 0; s < c.n_slots; ++s) owner[s] = -1;
     for (int e = 0; e < c.n_experts + c.n_shared; ++e) {
         const bool shared = e >= c.n_experts;
         const int32_t s = shared ? host_shared_slots[e - c.n_experts] : host_map[e];
@@ -306,11 +302,26 @@ moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t
             return fail(MOE_ERR_MAP, "%s %d -> slot %d is outside [%s, %d)", shared ? "shared expert" : "expert",
                         shared ? e - c.n_experts : e, s, shared ? "0" : "-1", c.n_slots);
         if (s >= 0) {
-            const moe_status_t st = claim_slot(c, owner, s, e);
-            if (st != MOE_OK) return st;
+            if (s >= c.n_slots)
+                return fail(MOE_ERR_MAP, "%s %d -> slot %d is outside [0, %d)", shared ? "shared expert" : "expert",
+                            shared ? e - c.n_experts : e, s, c.n_slots);
+            if (owner[s] >= 0) return fail(MOE_ERR_MAP, "slot %d is claimed twice (entries %d and %d)", s, owner[s], e);
+            owner[s] = e;
         }
         table[e] = s;
     }
+    return MOE_OK;
+}
+
+moe_status_t moe_set_expert_map(moe_layer_t *l, const int32_t *host_map, int32_t n,
+                                const int32_t *host_shared_slots, void *hip_stream)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    const moe_config_t &c = l->cfg;
+    std::vector<int32_t> owner(c.n_slots, -1);  // slot -> entry index that claimed it
+    std::vector<int32_t> table(c.n_experts + c.n_shared);
+    const moe_status_t st = validate_plain_map(c, host_map, n, host_shared_slots, table.data(), owner.data());
+    if (st != MOE_OK) return st;
     return install_table(l, table, owner, hip_stream);
 }
 
@@ -405,7 +416,7 @@ moe_status_t moe_workspace_view(const moe_layer_t *l, moe_workspace_view_t *v)
     v->inv = (const int32_t *)(ws + l->lay.inv);
     v->h = ws + l->lay.h;
     v->y = ws + l->lay.y;
-    v->active_map = (const int32_t *)(ws + l->lay.map[l->active]);
+    v->active_map = (const int32_t *)(ws + l->lay.map);
     v->tiles = (const int32_t *)(ws + l->lay.tiles);
     v->n_tiles = (const int32_t *)(ws + l->lay.n_tiles);
     return MOE_OK;
@@ -440,7 +451,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.x = x; p.out = out;
     p.router_w = l->buf.router_w; p.logit_bias = l->buf.logit_bias; p.select_bias = l->buf.select_bias;
     p.w13 = l->buf.w13; p.w2 = l->buf.w2;
-    p.map = (const int32_t *)(ws + l->lay.map[l->active]);
+    p.map = (const int32_t *)(ws + l->lay.map);
     p.logits = (float *)(ws + l->lay.logits);
     p.logit_planes = 1;
     // the kernels after the gate only read ids and w

@@ -88,32 +88,78 @@ class Case:
                               forced_ids=forced_ids, identity_experts=identity)
 
 
+def legal_selection(c_t: np.ndarray, ids: np.ndarray, k: int, n_group: int, topk_group: int):
+    """Is `ids` a selection the ordering rule allows for selection scores c_t once fp32 scores
+    closer than TIE count as equal?  Returns None when it is, else a sentence saying why not.
+
+    Groups (n_group > 1): a group's score is the fp32 sum of its two largest scores (its largest,
+    for groups of one).  With g_th the topk_group-th largest group score, a kept-group set is
+    legal when it holds every group scoring >= g_th + TIE, and otherwise only groups within TIE
+    of g_th, topk_group groups in all.  Inside a legal kept set the k ids must be its best
+    experts up to near-ties: no expert left out may beat a chosen one by TIE or more."""
+    import itertools
+    E = c_t.shape[0]
+    ids = [int(e) for e in ids]
+    if n_group > 1:
+        per = E // n_group
+        grp = np.sort(c_t.reshape(n_group, per), axis=1)
+        gs = (grp[:, -1] + grp[:, -2]).astype(np.float32) if per > 1 else grp[:, -1].copy()
+        g_th = np.sort(gs)[n_group - topk_group]
+        sure = [g for g in range(n_group) if gs[g] >= g_th + np.float32(TIE)]
+        near = [g for g in range(n_group) if abs(float(gs[g]) - float(g_th)) < TIE]
+        used = {e // per for e in ids}
+        stray = used - set(sure) - set(near)
+        if stray:
+            return f"ids come from groups {sorted(stray)} whose scores are not within {TIE} of the {topk_group}-th group score"
+        need = topk_group - len(sure)
+        options = [set(sure) | set(extra) for extra in itertools.combinations(near, need)] if 0 <= need <= len(near) else []
+        options = [K for K in options if used <= K]
+        if not options:
+            return f"groups {sorted(used)} fit no legal kept-group set (sure {sure}, near-tied {near})"
+    else:
+        per = E
+        options = [{0}]
+    why = None
+    for K in options:
+        members = np.array([e for e in range(E) if e // per in K])
+        chosen = np.zeros(E, bool)
+        chosen[ids] = True
+        left = members[~chosen[members]]
+        if left.size == 0:
+            return None
+        worst_in = float(c_t[ids].min())
+        best_out = float(c_t[left].max())
+        if best_out - worst_in < TIE:
+            return None
+        why = (f"expert {int(left[np.argmax(c_t[left])])} (score {best_out}) was left out although it beats "
+               f"a chosen one (score {worst_in}) by {best_out - worst_in:.3g}")
+    return why
+
+
 def check_routing(case: Case, gpu_ids: np.ndarray, gpu_w: np.ndarray):
-    """Routing parity: identical expert sets on every unflagged token; on flagged tokens a
-    difference must be a swap of candidates whose fp32 scores lie within TIE of the k-th
-    score.  Weights agree to W_ATOL * scale per expert.  Returns (ids to grade the output
-    with, number of flagged tokens, number of legal flips)."""
+    """Routing parity: identical expert sets on every unflagged token; on a flagged token
+    (expert near-tie, group near-tie, or both) a different set must still be a selection the
+    ordering rule allows when fp32 scores closer than TIE count as equal (legal_selection).
+    Weights agree to W_ATOL * scale per expert.  Returns (ids to grade the output with,
+    number of flagged tokens, number of legal flips)."""
     o_ids, o_w, flags, c = case.oracle_route()
     T, k = o_ids.shape
+    wl = case.wl
     assert gpu_ids.shape == (T, k)
-    assert (gpu_ids >= 0).all() and (gpu_ids < case.wl.n_experts).all()
+    assert (gpu_ids >= 0).all() and (gpu_ids < wl.n_experts).all()
     srt_g, srt_o = np.sort(gpu_ids, 1), np.sort(o_ids, 1)
     assert (np.diff(srt_g, axis=1) > 0).all(), "a token selected the same expert twice"
     differ = (srt_g != srt_o).any(1)
     bad = differ & (flags == 0)
     assert not bad.any(), f"routing differs on unflagged tokens {np.nonzero(bad)[0][:8]}"
+    grouped = wl.gate == "sigmoid_group" and wl.n_group > 1
     flips = 0
     for t in np.nonzero(differ)[0]:
-        only_g = set(gpu_ids[t]) - set(o_ids[t])
-        only_o = set(o_ids[t]) - set(gpu_ids[t])
-        kth = c[t, o_ids[t, -1]]
-        if flags[t] & 2:
-            continue  # group near-tie: whole groups may swap; output graded with the GPU's ids
-        for e in only_g | only_o:
-            assert abs(float(c[t, e]) - float(kth)) < TIE, (t, e, c[t, e], kth)
+        why = legal_selection(c[t], gpu_ids[t], k, wl.n_group if grouped else 1, wl.topk_group if grouped else 1)
+        assert why is None, f"token {t} (flags {int(flags[t])}): {why}"
         flips += 1
     # weights, matched per expert id (positions may differ among near-equal scores)
-    scale = abs(case.wl.routed_scale)
+    scale = abs(wl.routed_scale)
     same = ~differ
     og = np.argsort(gpu_ids, 1)
     oo = np.argsort(o_ids, 1)
@@ -172,18 +218,40 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.abs(got - want).max() / den)
 
 
+ROW_FLOOR = 1e-3   # a row's own scale counts down to this fraction of the largest reference magnitude
+
+
+def row_errors(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    """Per row: max |got - want| over the row / max |want| over THE ROW, the denominator floored at
+    ROW_FLOOR * max |want| over everything (a row that is almost zero is not held to its own scale)."""
+    if want.size == 0:
+        return np.zeros(0)
+    floor = ROW_FLOOR * np.abs(want).max()
+    den = np.maximum(np.abs(want).max(1), floor)
+    den[den == 0] = 1.0
+    return np.abs(got - want).max(1) / den
+
+
 def check_output(case: Case, out_bits: np.ndarray, grade_ids: np.ndarray, tokens=None, identity=False,
-                 shared_range=None):
+                 shared_range=None, report=None):
+    """Layer output against the fp64 oracle: the max-relative-error bar over all compared rows, and the
+    same bar row by row against each row's own largest reference magnitude.  report: a dict that
+    receives the two figures and the worst row."""
     want = case.oracle_forward(tokens=tokens, forced_ids=grade_ids, identity=identity, shared_range=shared_range)
     got = to_f64(out_bits if tokens is None else out_bits[np.asarray(tokens)])
     assert np.isfinite(got).all()
     err = rel_err(got, want)
     tol = TOL[case.wl.act_dtype]
     assert err <= tol, f"max relative error {err:.3e} > {tol}"
-    # per-row view of the same bar (rows whose reference is all zero must be exactly zero)
-    ref_max = np.abs(want).max(1)
-    zero = ref_max == 0
+    # rows whose reference is all zero must be exactly zero
+    zero = np.abs(want).max(1) == 0 if want.size else np.zeros(0, bool)
     assert (got[zero] == 0).all()
-    row_err = np.abs(got - want).max(1)[~zero] / np.abs(want).max()
-    assert row_err.max(initial=0.0) <= tol
+    rows = row_errors(got, want)
+    worst = int(np.argmax(rows)) if rows.size else -1
+    worst_tok = worst if tokens is None or worst < 0 else int(np.asarray(tokens)[worst])
+    print(f"[{case.wl.name}] rows graded {rows.size}  max rel err {err:.3e}  worst row: token {worst_tok} "
+          f"row err {rows.max(initial=0.0):.3e}", flush=True)
+    if report is not None:
+        report.update(rows=int(rows.size), err=err, worst_row_err=float(rows.max(initial=0.0)), worst_token=worst_tok)
+    assert rows.max(initial=0.0) <= tol, f"token {worst_tok}: row error {rows.max():.3e} > {tol}"
     return err

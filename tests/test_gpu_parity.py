@@ -16,7 +16,24 @@ def _case(wl, **kw):
     return Case(wl, **kw)
 
 
-def _full_check(case, flags=0, sample=None, T=None, shared_range=None):
+def _tile_sample(v, rows_per_tile, extra_tokens, T, seed):
+    """Tokens that cover EVERY M-tile of the pass: the first, the last and seeded random rows of each
+    tile (a tile-position mistake cannot hide between samples), plus seeded tokens drawn from the whole batch
+    (among them tokens with no local work, whose rows must be exactly zero)."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    rows = []
+    for _, r0, n, _ in v["tiles"]:
+        pick = {int(r0), int(r0 + n - 1)}
+        pick |= set(int(r) for r in r0 + g.choice(n, size=min(n, rows_per_tile), replace=False))
+        rows.extend(sorted(pick))
+    tok = set(int(t) for t in v["perm"][np.asarray(rows, np.int64)]) if rows else set()
+    tok |= set(int(t) for t in g.choice(T, size=min(T, extra_tokens), replace=False))
+    return np.array(sorted(tok), np.int32)
+
+
+def _full_check(case, flags=0, sample=None, T=None, shared_range=None, report=None):
+    """sample: None = every token is graded; an int = that many seeded tokens; ("tiles", r, x) = r rows of
+    every M-tile plus x tokens of the whole batch."""
     from gpu_util import check_routing, check_bookkeeping, check_output
     wl = case.wl
     T = wl.tokens if T is None else T
@@ -29,10 +46,12 @@ def _full_check(case, flags=0, sample=None, T=None, shared_range=None):
         grade_ids, n_flag, flips = None, 0, 0
     check_bookkeeping(case, v, T, sr)
     tokens = None if T == wl.tokens else np.arange(T, dtype=np.int32)
-    if sample is not None and sample < T:
+    if isinstance(sample, tuple):
+        tokens = _tile_sample(v, sample[1], sample[2], T, 1234 + wl.seed)
+    elif sample is not None and sample < T:
         g = np.random.Generator(np.random.PCG64(1234 + wl.seed))
         tokens = np.sort(g.choice(T, size=sample, replace=False)).astype(np.int32)
-    err = check_output(case, out, grade_ids, tokens=tokens, shared_range=sr)
+    err = check_output(case, out, grade_ids, tokens=tokens, shared_range=sr, report=report)
     return out, v, err
 
 
@@ -136,32 +155,39 @@ def test_shorter_batch_than_capacity_after_longer_one():
 
 # ---- the five benchmark configurations at full size ---------------------------
 
-def test_qwen3_shape_full_size_sampled():
+def test_qwen3_shape_full_size_all_tokens():
     case = _case(get_workload("qwen3_30b_a3b"))
-    _, v, err = _full_check(case, sample=48)
-    assert v["offsets"][-1] == 4096 * 8
+    rep = {}
+    _, v, err = _full_check(case, report=rep)
+    assert v["offsets"][-1] == 4096 * 8 and rep["rows"] == 4096
 
 
-def test_dsv3_rank_full_size_sampled():
+def test_dsv3_rank_full_size_every_tile():
+    """The largest configuration: 32 rows of every M-tile (36 chunks: whole rounds, the split last round, the
+    four chunks of the shared expert) and 256 tokens of the whole batch are graded, over 1024 tokens in all."""
     case = _case(get_workload("dsv3_ep8_rank"))
-    _full_check(case, sample=64)
+    rep = {}
+    _, v, _ = _full_check(case, sample=("tiles", 32, 256), report=rep)
+    assert rep["rows"] >= 1024 and len(v["tiles"]) >= 36
 
 
 def test_long_contraction_with_a_split_last_round():
     """288 one-chunk groups x one N-slice = 36 rows of 8 workgroups on a 32-row chip: the 4 rows of the last
     round have their contraction (H = 4096) shared out over 8 workgroups each and summed by a third launch.
-    Rows of every group are sampled, so tiles of the whole rounds and of the split round are both graded."""
+    Every token is graded, so tiles of the whole rounds and of the split round are all covered."""
     wl = MoEWorkload(name="splitk", tokens=1800, hidden=4096, inter=64, n_experts=288, top_k=8, n_slots=288,
                      n_local=288, act_dtype="bf16", router_dtype="bf16", gate="softmax", seed=17)
     case = _case(wl)
-    _, v, _ = _full_check(case, sample=160)
+    _, v, _ = _full_check(case)
     assert len(v["tiles"]) == 288 and v["counts"].min() > 0      # the launch shape the test is about
     assert wl.tokens * wl.top_k >= 48 * wl.n_slots               # ... on the large-tile kernels
 
 
-def test_dsv2_lite_shape_full_size_sampled():
+def test_dsv2_lite_shape_full_size_all_tokens():
     """third model shape of the paper's evaluation: 64 experts, top-6, no renormalisation, 2 shared experts"""
-    _full_check(_case(get_workload("dsv2_lite")), sample=64)
+    rep = {}
+    _full_check(_case(get_workload("dsv2_lite")), report=rep)
+    assert rep["rows"] == 4096
 
 
 def test_dsv3_decode_all_tokens():
@@ -175,7 +201,7 @@ def test_relayout_switch_keeps_buffers_and_matches_oracle():
     wl = get_workload("qwen3_relayout")
     map_a, map_b = relayout_maps(wl)
     case = _case(wl, expert_map=map_a)
-    _full_check(case, sample=48)
+    _full_check(case)                       # phase A, every token
     ptrs = (case.layer.w13.data_ptr(), case.layer.w2.data_ptr(), case.layer.workspace.data_ptr())
     free0, _ = torch.cuda.mem_get_info()
     alloc0 = torch.cuda.memory_stats()["allocation.all.allocated"]
@@ -189,7 +215,7 @@ def test_relayout_switch_keeps_buffers_and_matches_oracle():
     # the pool on the device now equals the pool the oracle was given
     from gpu_util import tensor_to_host
     np.testing.assert_array_equal(tensor_to_host(case.layer.w13[40:42]), case.w13_pool[40:42])
-    _full_check(case, sample=48)
+    _full_check(case)                       # phase B, every token
     assert alloc0 <= base_alloc
 
 
@@ -315,3 +341,93 @@ def test_configuration_limits():
                      n_slots=68, n_local=64, act_dtype="bf16", router_dtype="bf16", gate="sigmoid_group",
                      n_group=64, topk_group=40, routed_scale=1.5, n_shared=4, shared_range=(5, 77), seed=23)
     _full_check(_case(wl))
+
+
+def test_groups_of_one_expert():
+    """n_group = E: every group is a single expert and its score is that expert's score alone; keeping the
+    topk_group best groups and then the k best experts is plain top-k."""
+    wl = MoEWorkload(name="group1", tokens=300, hidden=256, inter=136, n_experts=32, top_k=4,
+                     n_slots=13, n_local=12, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=32, topk_group=9, routed_scale=1.5, n_shared=1,
+                     shared_range=(20, 280), seed=24)
+    case = _case(wl)
+    _, v, _ = _full_check(case)
+    plain = np.sort(np.argsort(-case.oracle_route()[3], axis=1, kind="stable")[:, :4], 1)
+    flagged = case.oracle_route()[2] != 0
+    np.testing.assert_array_equal(np.sort(v["topk_ids"], 1)[~flagged], plain[~flagged])
+
+
+def _permuted_placement_is_bit_identical(wl, seed, expect_kernel):
+    """The same layer with its experts in two different slot assignments (weights moved accordingly):
+    outputs must agree bit for bit -- where an expert sits must not change any row's arithmetic."""
+    case = _case(wl)
+    a = case.run()
+    v = case.layer.view(wl.tokens)
+    expect_kernel(wl, v)
+    g = np.random.Generator(np.random.PCG64(seed))
+    n_routed = wl.n_slots - wl.n_shared
+    slots = g.permutation(n_routed)[:min(wl.n_local, n_routed)].astype(np.int32)
+    assert not np.array_equal(slots, np.arange(slots.size))
+    case.place(block_expert_map(wl.n_experts, 0, slots.size, slots))
+    b = case.run()
+    np.testing.assert_array_equal(a, b)
+    return case
+
+
+def test_slot_permutation_bit_identical_large_tiles_multi_chunk_groups():
+    """Large-tile kernels with Zipf-skewed groups of up to a dozen chunks: chunk order in the tile list moves
+    with the placement, the rows' arithmetic must not."""
+    wl = MoEWorkload(name="perm8", tokens=4000, **{**SMALL, "inter": 128, "hidden": 320, "n_experts": 32, "n_slots": 40,
+                                                   "n_local": 32, "zipf_s": 1.2, "seed": 25})
+    def expect(wl, v):
+        assert wl.tokens * wl.top_k >= 48 * wl.n_slots and v["counts"].max() > 640
+    _permuted_placement_is_bit_identical(wl, 6, expect)
+
+
+def test_slot_permutation_bit_identical_weight_streaming_kernels():
+    wl = MoEWorkload(name="permd", tokens=24, hidden=264, inter=136, n_experts=32, top_k=4,
+                     n_slots=21, n_local=16, act_dtype="bf16", router_dtype="bf16",
+                     gate="sigmoid_group", n_group=4, topk_group=2, routed_scale=2.5, n_shared=1,
+                     shared_range=(2, 22), seed=26)
+    def expect(wl, v):
+        assert wl.tokens * wl.top_k <= 4 * wl.n_experts
+    _permuted_placement_is_bit_identical(wl, 7, expect)
+
+
+def test_slot_permutation_bit_identical_split_last_round():
+    """H = 4096 on the large-tile kernels with a last round whose tiles' contractions are shared out over
+    several workgroups: which tiles those are must not depend on the slots the experts sit in."""
+    wl = MoEWorkload(name="perms", tokens=1800, hidden=4096, inter=64, n_experts=288, top_k=8, n_slots=300,
+                     n_local=288, act_dtype="bf16", router_dtype="bf16", gate="softmax", seed=17)
+    def expect(wl, v):
+        assert len(v["tiles"]) == 288 and wl.tokens * wl.top_k >= 48 * wl.n_slots
+    _permuted_placement_is_bit_identical(wl, 8, expect)
+
+
+@pytest.mark.parametrize("experts", [16, 576])
+def test_fewer_candidates_than_k_stays_in_bounds(experts):
+    """A selection bias of -inf on all but two experts leaves a token two candidates for k = 4: the two are
+    selected with their renormalised scores, the other two positions carry weight 0 and an id inside [0, E),
+    and the output is the two experts' weighted sum (register and LDS selection paths)."""
+    import oracle
+    from gpu_util import to_f64, rel_err, TOL
+    wl = MoEWorkload(name="few_candidates", tokens=150, **{**SMALL, "n_experts": experts, "hidden": 128, "inter": 64,
+                                                             "n_slots": 16, "n_local": 16, "seed": 27})
+    sb = np.full(experts, -np.inf, np.float32)
+    sb[[2, 7]] = 0.0
+    case = _case(wl, select_bias=sb)
+    out = case.run()
+    v = case.layer.view(wl.tokens)
+    ids, w = v["topk_ids"], v["topk_w"]
+    assert (ids >= 0).all() and (ids < experts).all()
+    real = w != 0
+    assert (real.sum(1) == 2).all()
+    assert (np.sort(np.where(real, ids, -1), 1)[:, 2:] == [2, 7]).all()
+    np.testing.assert_allclose(w.sum(1), 1.0, atol=1e-5)
+    c = case.oracle_route()[3]                     # selection scores; experts 2 and 7 are un-biased
+    s2, s7 = c[:, 2].astype(np.float64), c[:, 7].astype(np.float64)
+    w2 = np.where((ids == 2) & real, w, 0).sum(1)
+    np.testing.assert_allclose(w2, s2 / (s2 + s7), atol=1e-5)
+    want = oracle.forward_routed(case.spec, case.inp["x"], case.w13_pool, case.w2_pool, case.expert_map,
+                                 np.where(real, ids, -1).astype(np.int32), w)
+    assert rel_err(to_f64(out), want) <= TOL["bf16"]

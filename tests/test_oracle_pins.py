@@ -173,6 +173,30 @@ def test_grouped_gate_brute_force_over_group_subsets():
     assert checked > 150
 
 
+def test_groups_of_one_expert_reduce_to_plain_topk():
+    """n_group = E: a group's score is its only expert's score, so keeping the topk_group >= k best
+    groups and then the k best experts is plain sigmoid top-k (library sort), and with topk_group = k
+    the kept groups ARE the selection."""
+    T, E = 120, 12
+    g = rnd(41)
+    x = g.standard_normal((T, E)).astype(np.float32)
+    wr = np.eye(E, dtype=np.float32)
+    s = scipy.special.expit(x.astype(np.float64)).astype(np.float32)
+    for k, kg in ((3, 5), (4, 4), (1, 12)):
+        spec = LayerSpec(T=T, H=E, I=1, E=E, k=k, S=E, gate="sigmoid_group", n_group=E, topk_group=kg)
+        ids, w, flags, c = oracle.route(spec, x, wr, want_scores=True)
+        np.testing.assert_array_equal(c, s)
+        want = np.argsort(-s, axis=1, kind="stable")[:, :k]
+        ok = flags == 0
+        assert ok.sum() > 100
+        np.testing.assert_array_equal(ids[ok], want[ok])
+        np.testing.assert_allclose(w.sum(1), 1.0, atol=1e-12)
+        # group flag (bit 1): the kg-th and (kg+1)-th SINGLE scores within 1e-5
+        srt = -np.sort(-s, axis=1)
+        if kg < E:
+            np.testing.assert_array_equal((flags >> 1) & 1, (srt[:, kg - 1] - srt[:, kg] < 1e-5).astype(np.uint8))
+
+
 def test_tie_break_lower_index_and_flag():
     # experts 1 and 3 have identical router rows -> identical scores for every token
     spec, x, wr, *_ = small_layer(8, T=30, E=4, k=1)
