@@ -248,6 +248,32 @@ moe_status_t moe_forward_routed(moe_layer_t *layer, const void *x, int32_t T,
                                 int32_t shared_begin, int32_t shared_end,
                                 void *out, void *hip_stream, uint32_t flags);
 
+/*
+ * moe_forward for callers that can neither allocate device memory nor hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  No layer
+ * object: the configuration, the weight buffers and the placement travel with the call, and every
+ * intermediate of the pass (expert table, routing, histograms, tile list, h, y) lives in a device
+ * array of MOE_STATIC_SCRATCH_BYTES that is part of the library image -- every GPU the library runs
+ * on holds one copy until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine) and never synchronises.
+ *   cfg, buf   as for moe_layer_create; buf->workspace and workspace_bytes are ignored (may be 0);
+ *              cfg->max_tokens only bounds T.
+ *   host_map [n], host_shared_slots   the placement, as for moe_set_expert_map (plain placements
+ *              only: one slot per expert); checked on every call, MOE_ERR_MAP as there.
+ *   x, T, shared range, out, hip_stream, flags   as for moe_forward.
+ * MOE_ERR_CAPACITY when a pass of T tokens of this layer needs more scratch than the array holds
+ * (moe_workspace_bytes of the configuration with max_tokens = T); nothing is launched then.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (a pass
+ * writes everything it reads, so nothing needs clearing): calls that overlap on one GPU -- on
+ * different streams, or from different host threads -- race; calls on one stream are ordered.
+ * The result is bit-identical to moe_forward on a layer of the same configuration and placement.
+ */
+#define MOE_STATIC_SCRATCH_BYTES (32u << 20)
+moe_status_t moe_forward_static(const moe_config_t *cfg, const moe_buffers_t *buf,
+                                const int32_t *host_map, int32_t n, const int32_t *host_shared_slots,
+                                const void *x, int32_t T, int32_t shared_begin, int32_t shared_end,
+                                void *out, void *hip_stream, uint32_t flags);
+
 /* Addresses of the intermediates (valid for the layer's lifetime). */
 moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *view);
 

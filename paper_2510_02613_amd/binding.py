@@ -25,7 +25,8 @@ EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
            "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
-           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy")
+           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_forward_static")
+MOE_STATIC_SCRATCH_BYTES = 32 << 20
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
 
@@ -85,6 +86,10 @@ def lib() -> ctypes.CDLL:
         L.moe_forward_routed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_uint32]
+        L.moe_forward_static.restype = ctypes.c_int
+        L.moe_forward_static.argtypes = [ctypes.POINTER(MoEConfig), ctypes.POINTER(MoEBuffers), ctypes.POINTER(ctypes.c_int32),
+                                         ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32]
         L.moe_load_expert.restype = ctypes.c_int
         L.moe_load_expert.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
@@ -177,6 +182,15 @@ def moe_forward(layer, x_ptr: int, T: int, out_ptr: int, shared_begin: int = 0, 
 def moe_forward_routed(layer, x_ptr: int, T: int, ids_ptr: int, w_ptr: int, out_ptr: int,
                        shared_begin: int = 0, shared_end: int = 0, stream: int = 0, flags: int = 0) -> None:
     _check(lib().moe_forward_routed(layer, ctypes.c_void_p(x_ptr), T, ctypes.c_void_p(ids_ptr), ctypes.c_void_p(w_ptr),
+                                    shared_begin, shared_end, ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream), flags))
+
+
+def moe_forward_static(cfg: MoEConfig, buf: MoEBuffers, host_map: Sequence[int], host_shared_slots: Optional[Sequence[int]],
+                       x_ptr: int, T: int, out_ptr: int, shared_begin: int = 0, shared_end: int = 0,
+                       stream: int = 0, flags: int = 0) -> None:
+    m, n = _i32_array(host_map)
+    s, ns = _i32_array(host_shared_slots)
+    _check(lib().moe_forward_static(ctypes.byref(cfg), ctypes.byref(buf), m, n, s if ns else None, ctypes.c_void_p(x_ptr), T,
                                     shared_begin, shared_end, ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream), flags))
 
 

@@ -8,12 +8,18 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "moe_internal.h"
 
 using namespace emoe;
+
+// Scratch of moe_forward_static: the whole workspace of its pass lives here, so that the call needs no
+// device memory from anybody.  One copy per GPU the library is loaded on, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
 
 namespace {
 thread_local char g_err[512] = "";
@@ -518,6 +524,76 @@ moe_status_t moe_forward_routed(moe_layer_t *layer, const void *x, int32_t T, co
     if (T > 0 && (!topk_ids || !topk_w)) return fail(MOE_ERR_ARG, "topk_ids and topk_w must be non-NULL");
     if (!aligned(topk_ids, 4) || !aligned(topk_w, 4)) return fail(MOE_ERR_ARG, "topk_ids and topk_w must be 4-byte aligned");
     return forward_pass(layer, x, T, topk_ids, topk_w, shared_begin, shared_end, out, hip_stream, flags);
+}
+
+// ---- moe_forward_static: the pass with every intermediate in the library's own device array ----
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, looked up once per device
+
+// Address of this GPU's copy of `scratch` (the current device's), found once per device.
+moe_status_t scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "device %d: moe_forward_static keeps scratch addresses for devices 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(MOE_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace
+
+moe_status_t moe_forward_static(const moe_config_t *cfg, const moe_buffers_t *buf,
+                                const int32_t *host_map, int32_t n, const int32_t *host_shared_slots,
+                                const void *x, int32_t T, int32_t shared_begin, int32_t shared_end,
+                                void *out, void *hip_stream, uint32_t flags)
+{
+    moe_status_t st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (T < 0) return fail(MOE_ERR_ARG, "T is negative");
+    if (T > cfg->max_tokens) return fail(MOE_ERR_CAPACITY, "T %d exceeds max_tokens %d", T, cfg->max_tokens);
+    // the workspace is laid out for THIS pass's T (max_tokens only bounds T): what must fit is the pass
+    moe_config_t c = *cfg;
+    c.max_tokens = T > 0 ? T : 1;
+    const Layout L = make_layout(c);
+    if (L.total > (size_t)MOE_STATIC_SCRATCH_BYTES)
+        return fail(MOE_ERR_CAPACITY, "a pass of %d tokens of this layer needs %zu bytes of scratch, moe_forward_static has %zu: "
+                    "use moe_forward with a workspace", T, L.total, (size_t)MOE_STATIC_SCRATCH_BYTES);
+    if (!buf) return fail(MOE_ERR_ARG, "buffers is NULL");
+    if (!buf->router_w || !buf->w13 || !buf->w2) return fail(MOE_ERR_ARG, "router_w, w13 and w2 must be non-NULL");
+    if (!aligned(buf->router_w, 16) || !aligned(buf->w13, 16) || !aligned(buf->w2, 16))
+        return fail(MOE_ERR_ARG, "router_w, w13 and w2 must be 16-byte aligned");
+    if ((buf->logit_bias && !aligned(buf->logit_bias, 4)) || (buf->select_bias && !aligned(buf->select_bias, 4)))
+        return fail(MOE_ERR_ARG, "bias vectors must be 4-byte aligned");
+    // the placement, checked like moe_set_expert_map does; tables on the host stack (E <= 1024, S <= 2047)
+    int32_t table[1024 + 4], owner[2048];
+    st = validate_plain_map(c, host_map, n, host_shared_slots, table, owner);
+    if (st != MOE_OK) return st;
+    if (T == 0) return MOE_OK;
+
+    void *ws = nullptr;
+    st = scratch_of_current_device(&ws);
+    if (st != MOE_OK) return st;
+    moe_layer lay;                       // host object on the stack: no heap, no device memory
+    lay.cfg = c;
+    lay.buf = *buf;
+    lay.buf.workspace = ws;              // kernels get the looked-up device address, never the symbol
+    lay.buf.workspace_bytes = MOE_STATIC_SCRATCH_BYTES;
+    lay.lay = L;
+    lay.has_map = true;
+    // every pass writes what it reads (table, histograms, tile list, h, y): nothing has to start at zero
+    const hipError_t e = launch_write_map((int32_t *)((char *)ws + L.map), table, c.n_experts + c.n_shared, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "expert map upload failed: %s", hipGetErrorString(e));
+    return forward_pass(&lay, x, T, nullptr, nullptr, shared_begin, shared_end, out, hip_stream, flags);
 }
 
 }  // extern "C"

@@ -147,6 +147,7 @@ class MoELayer:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.moe_set_expert_map(self.handle, list(expert_map),
                              None if shared_slots is None or len(shared_slots) == 0 else list(shared_slots), s.cuda_stream)
+        self.plain_map = ([int(v) for v in expert_map], None if shared_slots is None or len(shared_slots) == 0 else [int(v) for v in shared_slots])
 
     def set_expert_replicas(self, replicas: Sequence[Sequence[int]], shared_slots: Optional[Sequence[int]] = None,
                             stream: Optional[torch.cuda.Stream] = None) -> None:
@@ -171,6 +172,19 @@ class MoELayer:
         s = torch.cuda.current_stream(self.device) if stream is None else stream
         B.moe_forward(self.handle, x.data_ptr(), T, out.data_ptr(), int(shared_range[0]),
                       int(shared_range[1]), s.cuda_stream, flags)
+        return out
+
+    def forward_static(self, x: torch.Tensor, out: Optional[torch.Tensor] = None, shared_range=(0, 0),
+                       flags: int = 0, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """The same pass through moe_forward_static: this layer's configuration, weight buffers and last plain
+        placement, every intermediate in the library's own device array (this layer's workspace is not used)."""
+        assert x.dtype == self.elt and x.is_contiguous() and x.shape[1] == self.cfg.hidden
+        if out is None:
+            out = torch.empty_like(x)
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        buf = B.MoEBuffers(self.buf.router_w, self.buf.logit_bias, self.buf.select_bias, self.buf.w13, self.buf.w2, 0, 0)
+        B.moe_forward_static(self.cfg, buf, self.plain_map[0], self.plain_map[1], x.data_ptr(), x.shape[0], out.data_ptr(),
+                             int(shared_range[0]), int(shared_range[1]), s.cuda_stream, flags)
         return out
 
     def forward_routed(self, x: torch.Tensor, topk_ids: torch.Tensor, topk_w: torch.Tensor,
