@@ -106,15 +106,23 @@ __device__ __forceinline__ int rank_in_block(int slot, int32_t *hist, int S)
     return rank;
 }
 
+// A block's word per slot: rows of the slot in the block (<= 1024) in the low 16 bits, and above them
+// the thread (= assignment of the block) that is the block's first for the slot.
 __global__ __launch_bounds__(kHistThreads) void k_slot_hist(Pass p)
 {
-    extern __shared__ int32_t hist[];   // [S] rows per slot seen so far in this block
+    extern __shared__ int32_t hist[];   // [S] rows per slot seen so far in this block, the ranking's rows, then first[S]
     const int tid = threadIdx.x;
     const int a = blockIdx.x * kHistThreads + tid;
     const int slot = slot_of(p, a);
     const int rank = rank_in_block(slot, hist, p.S);
+    int32_t *first = hist + rank_lds_ints(p.S);
+    if (slot >= 0 && rank == 0) first[slot] = tid;     // one writer per slot with rows; slots without rows are not read
     if (a < p.T * p.kk) p.slot_rank[a] = slot >= 0 ? ((slot << 12) | rank) : -1;
-    for (int s = tid; s < p.S; s += kHistThreads) p.blk_hist[(size_t)blockIdx.x * p.S + s] = hist[s];
+    __syncthreads();
+    for (int s = tid; s < p.S; s += kHistThreads) {
+        const int c = hist[s];
+        p.blk_hist[(size_t)blockIdx.x * p.S + s] = c ? (c | (first[s] << 16)) : 0;
+    }
 }
 
 // exclusive scan of v over the NT threads of the block (v is per-thread), returns the
@@ -165,20 +173,29 @@ __device__ __forceinline__ void emit_tiles(const Pass &p, int s, int c, int nt, 
 constexpr int kSortMax = 2048;   // tile lists up to this long can be ordered by size (staged in LDS)
 constexpr int kSizeBins = 12;    // size classes: 32-row token tiles of a chunk, capped (even, scanned in pairs)
 
-// sort_tiles != 0: the tile list is left ordered by size class, largest first, ties in slot
-// order (longest-processing-time-first: the tail of a launch that is only a few rounds of the
-// chip deep then consists of the cheapest tiles).  Lists longer than kSortMax stay in slot order.
+constexpr int kMaxSlots = 2048;  // n_slots <= 2047
+
+// sort_tiles != 0: the tile list is left ordered by size class, largest first (longest-processing-time-
+// first: the tail of a launch that is only a few rounds of the chip deep then consists of the
+// cheapest tiles), and within a class by the FIRST ASSIGNMENT of the slot's group (the lowest
+// token-and-position that was routed to it), chunks of a group in row order.  Neither key depends on
+// which slot a group's expert sits in, so the order -- and with it which tiles the large-tile kernels
+// run in their split last round -- is the same under every placement of the same experts.  Lists
+// longer than kSortMax stay in slot order.
 __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, int tile_rows, int sort_tiles)
 {
     __shared__ int32_t scratch[8];
     __shared__ MTile staged[kSortMax];
     __shared__ int32_t bin_cnt[kSizeBins][kThreads + 1];
+    __shared__ int32_t fkey[kMaxSlots];      // first assignment of the slot's group (INT_MAX: no rows)
+    __shared__ int32_t srank[kMaxSlots];     // position of the slot when slots are ordered by fkey
+    __shared__ int32_t by_rank[kMaxSlots];   // tiles of the slot at that position, then their exclusive prefix sum
     const bool staging = sort_tiles && p.max_tiles <= kSortMax;
     const int tid = threadIdx.x;
     const int S = p.S;
     // 1. per slot: running sum over blocks (blk_hist becomes the block's exclusive base)
     for (int s = tid; s < S; s += kThreads) {
-        int run = 0;
+        int run = 0, key = 0x7fffffff;
         for (int b0 = 0; b0 < n_blocks; b0 += 16) {   // 16 loads in flight, then their running sum
             int c[16];
 #pragma unroll
@@ -186,25 +203,43 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 if (b0 + i < n_blocks) p.blk_hist[(size_t)(b0 + i) * S + s] = run;
-                run += c[i];
+                if (c[i] && key == 0x7fffffff) key = (b0 + i) * kAssignPerBlock + (c[i] >> 16);
+                run += c[i] & 0xffff;
             }
         }
         p.counts[s] = run;
+        fkey[s] = key;
     }
     __syncthreads();
-    // 2. exclusive scans over slots, in chunks of 256 slots: row offsets and tile offsets
+    // 2. the order tiles are emitted in: slot order, or (size-ordered lists) the order of the groups' first assignments
+    if (staging) {
+        for (int s = tid; s < S; s += kThreads) {
+            const int key = fkey[s];
+            int r = 0;
+            for (int o = 0; o < S; ++o) {
+                const int ko = fkey[o];
+                r += (ko < key) || (ko == key && o < s);   // keys of slots with rows are distinct; empty slots follow in slot order
+            }
+            srank[s] = r;
+        }
+    } else {
+        for (int s = tid; s < S; s += kThreads) srank[s] = s;
+    }
+    __syncthreads();
+    for (int s = tid; s < S; s += kThreads) by_rank[srank[s]] = (p.counts[s] + tile_rows - 1) / tile_rows;
+    __syncthreads();
+    // 3. exclusive scans in chunks of 256: row offsets over slots, tile offsets over positions
     int row_carry = 0, tile_carry = 0;
     for (int s0 = 0; s0 < S; s0 += kThreads) {
         const int s = s0 + tid;
         const int c = s < S ? p.counts[s] : 0;
-        const int nt = (c + tile_rows - 1) / tile_rows;
+        const int nt = s < S ? by_rank[s] : 0;
         int row_tot, tile_tot;
         const int row_off = row_carry + block_exclusive_scan(c, scratch, &row_tot);
         const int tile_off = tile_carry + block_exclusive_scan(nt, scratch, &tile_tot);
-        if (s < S) {
-            p.offs[s] = row_off;
-            emit_tiles(p, s, c, nt, row_off, tile_off, tile_rows, staging ? staged : p.tiles);
-        }
+        if (s < S) p.offs[s] = row_off;
+        __syncthreads();
+        if (s < S) by_rank[s] = tile_off;          // position s: first tile of the slot that holds it
         row_carry += row_tot;
         tile_carry += tile_tot;
     }
@@ -212,8 +247,13 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
         p.offs[S] = row_carry;
         *p.n_tiles = min(tile_carry, p.max_tiles);
     }
+    __syncthreads();
+    for (int s = tid; s < S; s += kThreads) {
+        const int c = p.counts[s];
+        emit_tiles(p, s, c, (c + tile_rows - 1) / tile_rows, p.offs[s], by_rank[srank[s]], tile_rows, staging ? staged : p.tiles);
+    }
     if (!staging) return;
-    // 3. stable counting sort of the staged list by size class, descending.  Thread t owns the
+    // 4. stable counting sort of the staged list by size class, descending.  Thread t owns the
     // contiguous index range [t*per_thread, (t+1)*per_thread): counts per (class, thread), an
     // exclusive scan over (class descending, thread ascending), then placement in index order.
     __syncthreads();
@@ -316,7 +356,7 @@ hipError_t launch_permute(const Pass &p, int tile_rows, bool sort_tiles, hipStre
         hipLaunchKernelGGL(k_permute_one_block, dim3(1), dim3(kHistThreads), one_block_lds, st, p, tile_rows);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * rank_lds_ints(p.S), st, p);
+    hipLaunchKernelGGL(k_slot_hist, dim3(nb), dim3(kHistThreads), sizeof(int32_t) * (rank_lds_ints(p.S) + p.S), st, p);
     hipLaunchKernelGGL(k_slot_scan, dim3(1), dim3(kThreads), 0, st, p, nb, tile_rows, sort_tiles ? 1 : 0);
     hipLaunchKernelGGL(k_slot_place, dim3(nbp), dim3(kThreads), 0, st, p);
     return hipGetLastError();
