@@ -120,6 +120,7 @@ def parse_args():
     ap.add_argument("--virtual-pool", action="store_true",
                     help="back the two weight pools with contiguous virtual tensors over separately allocated physical "
                          "pages (moe_vpool_*), pages mapped in a shuffled order, instead of plain allocations")
+    ap.add_argument("--flags", type=int, default=0, help="MOE_FLAG_* bits passed to every forward (testing aids of the library)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measuring-stick kernels (sustained MFMA rate, streaming read) after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -194,7 +195,7 @@ def run_workload(torch, args, name, extras=False):
     stream = torch.cuda.current_stream(dev)
 
     def step():
-        layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream)
+        layer.forward(x, out=out, shared_range=wl.shared_range, stream=stream, flags=args.flags)
 
     for _ in range(args.warmup):
         step()

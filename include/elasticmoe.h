@@ -124,6 +124,8 @@ typedef struct {
 #define MOE_FLAG_IDENTITY_EXPERTS 1u /* test mode: every expert returns its input row unchanged */
 #define MOE_FLAG_FORCE_GENERIC    2u /* run the plain (non-MFMA) expert kernels: debugging aid */
 #define MOE_FLAG_GATE_TILED       4u /* bf16 activations: use the LDS-tiled gate logits kernel at any batch size (testing aid) */
+#define MOE_FLAG_PERMUTE_UNFUSED  8u /* rank the assignments in the separate histogram kernels (the path of passes whose routing is
+                                      * given and of batches over 8192 tokens) instead of inside the selection kernel (testing aid) */
 
 /*
  * Bytes of device workspace a layer of this configuration needs (0 if cfg is

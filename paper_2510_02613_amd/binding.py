@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libelasticmoe.so")
 MOE_OK, MOE_ERR_ARG, MOE_ERR_SHAPE, MOE_ERR_MAP, MOE_ERR_CAPACITY, MOE_ERR_UNSUPPORTED, MOE_ERR_HIP = range(7)
 MOE_F32, MOE_BF16 = 0, 1
 MOE_GATE_SOFTMAX_TOPK, MOE_GATE_SIGMOID_GROUP_TOPK = 0, 1
-MOE_FLAG_IDENTITY_EXPERTS, MOE_FLAG_FORCE_GENERIC, MOE_FLAG_GATE_TILED = 1, 2, 4
+MOE_FLAG_IDENTITY_EXPERTS, MOE_FLAG_FORCE_GENERIC, MOE_FLAG_GATE_TILED, MOE_FLAG_PERMUTE_UNFUSED = 1, 2, 4, 8
 
 STATUS_NAMES = {0: "MOE_OK", 1: "MOE_ERR_ARG", 2: "MOE_ERR_SHAPE", 3: "MOE_ERR_MAP",
                 4: "MOE_ERR_CAPACITY", 5: "MOE_ERR_UNSUPPORTED", 6: "MOE_ERR_HIP"}

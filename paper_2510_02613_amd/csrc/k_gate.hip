@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "moe_internal.h"
+#include "wave_ops.h"
 
 namespace emoe {
 
@@ -38,78 +39,12 @@ __device__ __forceinline__ unsigned long long make_key(float score, int idx)
 }
 __device__ __forceinline__ int key_index(unsigned long long key) { return (int)(0xffffffffu - (uint32_t)(key & 0xffffffffull)); }
 
-// Wavefront reductions on the DPP network (no LDS round trips): row_shr 1,2,4,8 leave each row's
-// result in its lane 15, row_bcast15 / row_bcast31 carry it across rows, lane 63 ends up with the
-// whole wavefront's result, which is then read back as a scalar.  Lanes without a source take the
-// operation's identity.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ int dpp_i32(int identity, int v)
-{
-    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
-}
-#define EMOE_DPP_REDUCE(STEP)                                                             \
-    STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) /* row_shr 1,2,4,8 */ \
-    STEP(0x142, 0xa) STEP(0x143, 0xc)                                   /* row_bcast15, 31 */
-
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
-{
-    unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
-#define STEP(CTRL, MASK)                                                                   \
-    {                                                                                      \
-        const unsigned ohi = (unsigned)dpp_i32<CTRL, MASK>(0, (int)hi);                    \
-        const unsigned olo = (unsigned)dpp_i32<CTRL, MASK>(0, (int)lo);                    \
-        const bool take = ohi > hi || (ohi == hi && olo > lo);                             \
-        hi = take ? ohi : hi;                                                              \
-        lo = take ? olo : lo;                                                              \
-    }
-    EMOE_DPP_REDUCE(STEP)
-#undef STEP
-    hi = (unsigned)__builtin_amdgcn_readlane((int)hi, 63);
-    lo = (unsigned)__builtin_amdgcn_readlane((int)lo, 63);
-    return ((unsigned long long)hi << 32) | lo;
-}
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-#define STEP(CTRL, MASK) { const uint32_t o = (uint32_t)dpp_i32<CTRL, MASK>(0, (int)v); v = o > v ? o : v; }
-    EMOE_DPP_REDUCE(STEP)
-#undef STEP
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-__device__ __forceinline__ int wave_min_i32(int v)
-{
-#define STEP(CTRL, MASK) { const int o = dpp_i32<CTRL, MASK>(0x7fffffff, v); v = o < v ? o : v; }
-    EMOE_DPP_REDUCE(STEP)
-#undef STEP
-    return __builtin_amdgcn_readlane(v, 63);
-}
-__device__ __forceinline__ float wave_max_f32(float v)
-{
-    const int ninf = (int)0xff800000u;
-#define STEP(CTRL, MASK) v = fmaxf(v, __int_as_float(dpp_i32<CTRL, MASK>(ninf, __float_as_int(v))));
-    EMOE_DPP_REDUCE(STEP)
-#undef STEP
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-// Orders this wavefront's LDS traffic: writes before it are visible to every lane after it.
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-__device__ __forceinline__ float wave_sum_f32(float v)
-{
-#define STEP(CTRL, MASK) v += __int_as_float(dpp_i32<CTRL, MASK>(0, __float_as_int(v)));
-    EMOE_DPP_REDUCE(STEP)
-#undef STEP
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-
 // Phase 2 for one token, run by one wavefront.
 //   lg   : LDS [E] logits in, scores out
 //   cs   : LDS [E] selection scores (biased), destroyed (taken entries -> -inf)
 //   gsc  : LDS [n_group] group scores
-__device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *gsc, int lane)
+// Returns the expert this lane holds (lane j < k: the j-th selected), which is also written to p.ids.
+__device__ int select_token(const Pass &p, int t, float *lg, float *cs, float *gsc, int lane)
 {
     const int E = p.E;
     const float NEG = -__builtin_huge_valf();
@@ -230,6 +165,7 @@ __device__ void select_token(const Pass &p, int t, float *lg, float *cs, float *
         p.ids[(size_t)t * p.k + lane] = my_id;
         p.w[(size_t)t * p.k + lane] = wv * p.routed_scale;
     }
+    return my_id;
 }
 
 template <typename XT, typename WT>
@@ -649,6 +585,70 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
     select_token(p, t, lg, cs, gsc, lane);
 }
 
+// The selection kernel with the first step of the routing bookkeeping fused in: a workgroup of 16
+// wavefronts owns kFusedTokens = 16 consecutive tokens, one per wavefront.  After the selection every
+// lane j < k + n_shared holds one assignment of its token; its slot is looked up in the expert table and
+// the workgroup builds, per slot, the 16-bit mask of its tokens that have a row in the slot (a token's
+// assignments go to distinct slots: distinct experts, one-to-one table), from which an assignment's rank
+// among the block's earlier rows of the slot is a population count -- deterministic, token order.
+// Word [slot][block] of blk_hist: the mask, and above it (bits 16..21) the selection position of the
+// block's first row in the slot (with the token it makes the group's first-assignment key); byte
+// [slot][block] of blk_cnt: the number of rows, i.e. of mask bits.
+__global__ __launch_bounds__(kFusedTokens * 64) void k_gate_select_hist(Pass p, int n_blocks)
+{
+    extern __shared__ float smem[];
+    const int E = p.E, S = p.S;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *lg = smem + wave * (2 * E + 64);   // [E] logits -> scores
+    float *cs = lg + E;                       // [E] selection scores
+    float *gsc = cs + E;                      // [64]
+    uint32_t *blkmask = (uint32_t *)(smem + kFusedTokens * (2 * E + 64));   // [S]
+    for (int s = threadIdx.x; s < S; s += kFusedTokens * 64) blkmask[s] = 0u;
+    const int t = blockIdx.x * kFusedTokens + wave;
+    int slot = -1;
+    if (t < p.T) {
+        for (int e = lane; e < E; e += 64) {
+            // partial sums of the K ranges: all planes are requested at once, then added in K order
+            float part[kGatePlanes];
+#pragma unroll
+            for (int z = 0; z < kGatePlanes; ++z) part[z] = z < p.logit_planes ? p.logits[((size_t)z * p.T + t) * E + e] : 0.f;
+            float v = part[0];
+#pragma unroll
+            for (int z = 1; z < kGatePlanes; ++z)
+                if (z < p.logit_planes) v += part[z];
+            lg[e] = v;
+        }
+        wave_sync();
+        const int id = select_token(p, t, lg, cs, gsc, lane);
+        if (lane < p.k) {
+            const int m = p.map[id];
+            if (m >= -1) {
+                slot = m;
+            } else {   // an expert with several copies: token t uses copy t mod R of the list behind the table's entries
+                const int32_t *copies = p.map + p.E + p.n_shared + (-2 - m);
+                slot = copies[1 + t % copies[0]];
+            }
+        } else if (lane < p.kk && t >= p.shared_begin && t < p.shared_end) {
+            slot = p.map[p.E + (lane - p.k)];
+        }
+    }
+    __syncthreads();
+    if (slot >= 0) atomicOr(&blkmask[slot], 1u << wave);
+    __syncthreads();
+    int rank = 0;
+    if (slot >= 0) {
+        rank = __popc(blkmask[slot] & ((1u << wave) - 1u));
+        if (rank == 0) atomicOr(&blkmask[slot], (uint32_t)lane << 16);   // one such lane per slot
+    }
+    if (t < p.T && lane < p.kk) p.slot_rank[(size_t)t * p.kk + lane] = slot >= 0 ? ((slot << 12) | rank) : -1;
+    __syncthreads();
+    for (int s = threadIdx.x; s < S; s += kFusedTokens * 64) {
+        const uint32_t m = blkmask[s];
+        p.blk_hist[(size_t)s * fused_row_stride(n_blocks) + blockIdx.x] = (int32_t)m;
+        p.blk_cnt[(size_t)s * fused_row_stride(n_blocks) + blockIdx.x] = (uint8_t)__popc(m & 0xffffu);   // what the placing kernel adds up
+    }
+}
+
 template <typename WT, int TT, int ET, bool KSPLIT>
 hipError_t launch_gate_logits_t(const Pass &p, int planes, hipStream_t st)
 {
@@ -680,6 +680,16 @@ hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
     else                                e = launch_gate_logits_lds<WT, 2, 1>(p, st);   // 32 tokens x 64 experts
     if (e != hipSuccess) return e;
     p.logit_planes = planes;
+    if (p.fused_hist) {
+        const int nb = (p.T + kFusedTokens - 1) / kFusedTokens;
+        const size_t smem = sizeof(float) * kFusedTokens * (2 * (size_t)p.E + 64) + sizeof(uint32_t) * p.S;
+        if (smem > 64 * 1024) {
+            e = hipFuncSetAttribute((const void *)k_gate_select_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(k_gate_select_hist, dim3(nb), dim3(kFusedTokens * 64), smem, st, p, nb);
+        return hipGetLastError();
+    }
     const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);
     hipLaunchKernelGGL(k_gate_select, dim3((p.T + 3) / 4), dim3(kThreads), smem, st, p);
     return hipGetLastError();

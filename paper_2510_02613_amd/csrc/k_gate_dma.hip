@@ -320,7 +320,7 @@ hipError_t launch_gate_logits_dma(const Pass &p, int *planes, hipStream_t st)
     // 128 x 256 (bf16 router) or 128 x 128 (fp32 router) on 8 wavefronts (2 x 4) with two rings: 4 stages of
     // token rows (16 KB each), 3 of router rows (32 KB each); 64 x 128 on 8 wavefronts and 32 x 64 on 4, one ring
     if (p.router_bf16) return cfg == 2 ? launch_t<uint16_t, 4, 4, 4, 8, 2, 3>(p, z, st) : cfg == 1 ? launch_t<uint16_t, 2, 2, 6, 8, 2>(p, z, st) : launch_t<uint16_t, 2, 1, 6, 4, 1>(p, z, st);
-    return cfg == 2 ? launch_t<float, 4, 2, 4, 8, 2, 3>(p, z, st) : cfg == 1 ? launch_t<float, 2, 2, 4, 8, 2>(p, z, st) : launch_t<float, 2, 1, 6, 4, 1>(p, z, st);
+    return cfg == 2 ? launch_t<float, 4, 2, 4, 8, 2, 3>(p, z, st) : cfg == 1 ? launch_t<float, 4, 1, 4, 8, 1>(p, z, st) : launch_t<float, 2, 1, 6, 4, 1>(p, z, st);
 }
 
 }  // namespace emoe

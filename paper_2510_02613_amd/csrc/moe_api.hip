@@ -51,7 +51,7 @@ constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: siz
 
 // Offsets of every intermediate inside the workspace.
 struct Layout {
-    size_t map, logits, ids, w, slot_rank, blk_hist, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
+    size_t map, logits, ids, w, slot_rank, blk_hist, blk_cnt, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
     bool has_partials;
 };
 
@@ -102,7 +102,11 @@ Layout make_layout(const moe_config_t &c)
     L.ids = take(4 * T * k);
     L.w = take(4 * T * k);
     L.slot_rank = take(4 * A);
-    L.blk_hist = take(4 * nb * S);
+    // block words of the bookkeeping: [blocks of 1024 assignments][S], or (fused with the selection) [S][blocks of 16 tokens]
+    const size_t nbf = ((T < (size_t)kFusedMaxTokens ? T : (size_t)kFusedMaxTokens) + kFusedTokens - 1) / kFusedTokens;
+    const size_t fused_words = (size_t)fused_row_stride((int)nbf) * S;
+    L.blk_hist = take(4 * (nb * S > fused_words ? nb * S : fused_words));
+    L.blk_cnt = take(fused_words);
     L.counts = take(4 * S);
     L.offs = take(4 * (S + 1));
     L.perm = take(4 * A);
@@ -438,7 +442,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     if (T > c.max_tokens) return fail(MOE_ERR_CAPACITY, "T %d exceeds max_tokens %d", T, c.max_tokens);
     if (shared_begin < 0 || shared_begin > shared_end || shared_end > T)
         return fail(MOE_ERR_ARG, "shared range [%d,%d) is not inside [0,%d]", shared_begin, shared_end, T);
-    if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC | MOE_FLAG_GATE_TILED)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
+    if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC | MOE_FLAG_GATE_TILED | MOE_FLAG_PERMUTE_UNFUSED)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
     if (!l->has_map) return fail(MOE_ERR_MAP, "no expert map installed: call moe_set_expert_map first");
     if (T == 0) return MOE_OK;
     if (!x || !out) return fail(MOE_ERR_ARG, "x and out must be non-NULL");
@@ -465,6 +469,7 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.w = routed_w ? const_cast<float *>(routed_w) : (float *)(ws + l->lay.w);
     p.slot_rank = (int32_t *)(ws + l->lay.slot_rank);
     p.blk_hist = (int32_t *)(ws + l->lay.blk_hist);
+    p.blk_cnt = (uint8_t *)(ws + l->lay.blk_cnt);
     p.counts = (int32_t *)(ws + l->lay.counts);
     p.offs = (int32_t *)(ws + l->lay.offs);
     p.perm = (int32_t *)(ws + l->lay.perm);
@@ -476,6 +481,8 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.partials = l->lay.has_partials ? (float *)(ws + l->lay.partials) : nullptr;
 
     p.gate_tiled = (flags & MOE_FLAG_GATE_TILED) != 0;
+    // gated bf16 passes up to kFusedMaxTokens tokens: the selection kernel ranks the assignments, one more kernel places them
+    p.fused_hist = p.act_bf16 && !routed_ids && T <= kFusedMaxTokens && !(flags & MOE_FLAG_PERMUTE_UNFUSED);
     const bool identity = flags & MOE_FLAG_IDENTITY_EXPERTS;
     const bool mfma = p.act_bf16 && !(flags & MOE_FLAG_FORCE_GENERIC);
     // large tiles once groups average at least a few MFMA tiles of rows

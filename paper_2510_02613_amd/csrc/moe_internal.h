@@ -40,7 +40,8 @@ struct Pass {
     int32_t *ids;        // [T,k]
     float *w;            // [T,k]
     int32_t *slot_rank;  // [T*kk] (slot << 12 | rank-in-block) or -1
-    int32_t *blk_hist;   // [NB,S] per-block histogram, then per-block exclusive base
+    int32_t *blk_hist;   // [NB,S] per-block histogram, then per-block exclusive base (fused bookkeeping: [S][row stride] token masks)
+    uint8_t *blk_cnt;    // fused bookkeeping: [S][row stride] rows per slot and block of 16 tokens
     int32_t *counts;     // [S]
     int32_t *offs;       // [S+1]
     int32_t *perm;       // [A]
@@ -51,6 +52,8 @@ struct Pass {
     void *y;             // [A,H]
     int32_t max_tiles;
     int32_t gate_tiled;  // the LDS-tiled gate logits kernel is forced (testing aid)
+    int32_t fused_hist;  // the selection kernel also ranks the assignments (blocks of kFusedTokens tokens, blk_hist [S][blocks]
+                         // of token masks); the scan-and-place kernel finishes the bookkeeping
     float *partials;     // partial sums of the large-tile GEMMs' split tiles, or NULL (no room: never split)
     int32_t n_cus;       // compute units of the device (set by the large-tile launcher)
     int32_t k_split;     // this launch may share the contraction of its last round's tiles out (set by the launcher)
@@ -58,6 +61,10 @@ struct Pass {
 
 constexpr int kGatePlanes = 8;         // partial-sum planes of the gate logits the workspace has room for
 constexpr int kAssignPerBlock = 1024;  // assignments ranked by one block of the slot histogram kernel
+constexpr int kFusedTokens = 16;       // tokens per workgroup of the fused selection + ranking kernel (one per wavefront)
+constexpr int kFusedMaxTokens = 8192;  // largest batch the fused bookkeeping serves: every placing workgroup reads all block masks
+// words between the rows of blk_hist [S][blocks] in the fused bookkeeping: whole groups of 64 blocks
+__host__ __device__ constexpr int fused_row_stride(int n_blocks) { return (n_blocks + 63) / 64 * 64; }
 
 hipError_t launch_write_map(int32_t *dst, const int32_t *host_vals, int n, hipStream_t st);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, int blocks, hipStream_t st);  // bytes % 16 == 0

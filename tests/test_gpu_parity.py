@@ -436,3 +436,11 @@ def test_fewer_candidates_than_k_stays_in_bounds(experts):
     want = oracle.forward_routed(case.spec, case.inp["x"], case.w13_pool, case.w2_pool, case.expert_map,
                                  np.where(real, ids, -1).astype(np.int32), w)
     assert rel_err(to_f64(out), want) <= TOL["bf16"]
+
+
+def test_largest_fp32_router_gate_tiling():
+    """8192 tokens with an fp32 router: the gate logits run on the largest token x expert tiling of the
+    direct-to-LDS kernel (128 x 128, rings for token and router rows); routing graded on every token."""
+    wl = MoEWorkload(name="gate128", tokens=8192, hidden=256, inter=64, n_experts=128, top_k=4, n_slots=9,
+                     n_local=8, act_dtype="bf16", router_dtype="f32", gate="softmax", seed=28)
+    _full_check(_case(wl), sample=256)

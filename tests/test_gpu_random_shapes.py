@@ -128,3 +128,12 @@ def _check(wl, emap, local):
     ids, _, _ = check_routing(case, v["topk_ids"], v["topk_w"])
     check_bookkeeping(case, v, wl.tokens, wl.shared_range)
     check_output(case, out, ids)
+    # the same pass with the assignments ranked by the separate histogram kernels (the path of routed passes and
+    # of very large batches) instead of inside the selection kernel: same bookkeeping, same bits
+    from paper_2510_02613_amd.binding import MOE_FLAG_PERMUTE_UNFUSED
+    out2 = case.run(flags=MOE_FLAG_PERMUTE_UNFUSED)
+    v2 = case.layer.view(wl.tokens)
+    check_bookkeeping(case, v2, wl.tokens, wl.shared_range)
+    for key in ("topk_ids", "counts", "offsets", "perm", "inv"):
+        np.testing.assert_array_equal(v[key], v2[key])
+    np.testing.assert_array_equal(out, out2)
