@@ -343,6 +343,30 @@ moe_status_t moe_vpool_unmap(moe_vpool_t *pool, int32_t vslot);
 int32_t moe_vpool_page_of(const moe_vpool_t *pool, int32_t vslot);
 moe_status_t moe_vpool_destroy(moe_vpool_t *pool);
 
+/*
+ * Zero-copy attach of a weight pool from another process (paper: the zero-copy primitive, Sec. 4.6; its
+ * export_handle / open_tensor pair, App. D; the serving instances of Sec. 3.2 that hold references to
+ * tensors kept by the memory daemon).  The process that owns a pool exports a handle; a serving process
+ * on the same GPU opens it and passes the address as moe_buffers_t.w13 / .w2: no weight byte is copied,
+ * and serving processes come and go while the owner keeps the experts resident.
+ *   moe_pool_export  dev_ptr: an address inside a device allocation of THIS process (e.g. the base of a
+ *                    pool).  handle receives MOE_IPC_HANDLE_BYTES opaque bytes that name the whole
+ *                    allocation, *offset the distance of dev_ptr from its start; both travel to the other
+ *                    process by any means (pipe, socket, file).  MOE_ERR_UNSUPPORTED for allocations of
+ *                    2 GiB and more (split such a pool over several allocations).
+ *   moe_pool_open    in the OTHER process: maps the allocation and returns the address that corresponds
+ *                    to dev_ptr.  The memory stays owned by the exporter, which must keep it allocated
+ *                    while it is open elsewhere; writes by either side are seen by the other (stream and
+ *                    process synchronisation are the callers').
+ *   moe_pool_close   unmaps it again (same address and offset as returned / given to moe_pool_open).
+ * A handle cannot be opened in the process that exported it.  Pools of moe_vpool_* are not exportable
+ * through these calls.
+ */
+#define MOE_IPC_HANDLE_BYTES 64
+moe_status_t moe_pool_export(const void *dev_ptr, void *handle, size_t *offset);
+moe_status_t moe_pool_open(const void *handle, size_t offset, void **dev_ptr);
+moe_status_t moe_pool_close(void *dev_ptr, size_t offset);
+
 /* Frees the host object only (the library owns no device memory). NULL is allowed. */
 void moe_layer_destroy(moe_layer_t *layer);
 

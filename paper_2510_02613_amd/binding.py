@@ -25,7 +25,9 @@ EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
            "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
-           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_forward_static")
+           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_forward_static",
+           "moe_pool_export", "moe_pool_open", "moe_pool_close")
+MOE_IPC_HANDLE_BYTES = 64
 MOE_STATIC_SCRATCH_BYTES = 32 << 20
 MOE_N_PHASES = 5
 PHASE_NAMES = ("gate", "permute", "gemm1", "gemm2", "combine")
@@ -108,6 +110,12 @@ def lib() -> ctypes.CDLL:
         L.moe_vpool_page_of.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.moe_vpool_destroy.restype = ctypes.c_int
         L.moe_vpool_destroy.argtypes = [ctypes.c_void_p]
+        L.moe_pool_export.restype = ctypes.c_int
+        L.moe_pool_export.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.POINTER(ctypes.c_size_t)]
+        L.moe_pool_open.restype = ctypes.c_int
+        L.moe_pool_open.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_void_p)]
+        L.moe_pool_close.restype = ctypes.c_int
+        L.moe_pool_close.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
         L.moe_workspace_view.restype = ctypes.c_int
         L.moe_workspace_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(MoEWorkspaceView)]
         L.moe_layer_destroy.restype = None
@@ -234,6 +242,25 @@ def moe_vpool_page_of(pool, vslot: int) -> int:
 
 def moe_vpool_destroy(pool) -> None:
     _check(lib().moe_vpool_destroy(pool))
+
+
+def moe_pool_export(dev_ptr: int):
+    """(handle bytes, offset) that name dev_ptr for another process."""
+    handle = ctypes.create_string_buffer(MOE_IPC_HANDLE_BYTES)
+    off = ctypes.c_size_t()
+    _check(lib().moe_pool_export(ctypes.c_void_p(dev_ptr), handle, ctypes.byref(off)))
+    return handle.raw, int(off.value)
+
+
+def moe_pool_open(handle: bytes, offset: int) -> int:
+    assert len(handle) == MOE_IPC_HANDLE_BYTES
+    p = ctypes.c_void_p()
+    _check(lib().moe_pool_open(ctypes.create_string_buffer(handle, MOE_IPC_HANDLE_BYTES), ctypes.c_size_t(offset), ctypes.byref(p)))
+    return int(p.value)
+
+
+def moe_pool_close(dev_ptr: int, offset: int) -> None:
+    _check(lib().moe_pool_close(ctypes.c_void_p(dev_ptr), ctypes.c_size_t(offset)))
 
 
 def moe_workspace_view(layer) -> MoEWorkspaceView:

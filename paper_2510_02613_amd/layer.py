@@ -66,6 +66,31 @@ class VirtualPool:
             self.handle = None
 
 
+class AttachedPool:
+    """A weight pool that lives in ANOTHER process's device memory, opened through its exported handle
+    (moe_pool_open): `tensor` is a torch view [n_vslots, *slot_shape] of it, nothing is copied or owned."""
+
+    def __init__(self, handle: bytes, offset: int, n_vslots: int, slot_shape, elt: torch.dtype, device="cuda:0"):
+        self.device = torch.device(device)
+        self.n_vslots, self.slot_shape, self.elt, self.offset = n_vslots, tuple(slot_shape), elt, offset
+        with torch.cuda.device(self.device):
+            self.ptr = B.moe_pool_open(handle, offset)
+        typestr = {torch.int16: "<i2", torch.float32: "<f4"}[elt]
+        self.tensor = torch.as_tensor(_DeviceSpan(self.ptr, (n_vslots,) + self.slot_shape, typestr), device=self.device)
+
+    def close(self) -> None:
+        if getattr(self, "ptr", None):
+            self.tensor = None
+            B.moe_pool_close(self.ptr, self.offset)
+            self.ptr = None
+
+
+def export_pool(t: torch.Tensor):
+    """(handle bytes, offset) of a pool tensor of this process, for AttachedPool in another process."""
+    assert t.is_contiguous() and t.is_cuda
+    return B.moe_pool_export(t.data_ptr())
+
+
 class MoELayer:
     """One layer over caller-visible torch buffers.
 

@@ -220,3 +220,16 @@ def test_virtual_pool_argument_checks_and_no_gpu():
         with pytest.raises(B.MoEError) as ei:      # no device: nothing to reserve addresses on
             B.moe_vpool_create(4096, 4)
         assert ei.value.status in (B.MOE_ERR_HIP, B.MOE_ERR_UNSUPPORTED)
+
+
+def test_pool_export_argument_checks():
+    import ctypes
+    L = B.lib()
+    h = ctypes.create_string_buffer(B.MOE_IPC_HANDLE_BYTES)
+    off = ctypes.c_size_t()
+    assert L.moe_pool_export(None, h, ctypes.byref(off)) == B.MOE_ERR_ARG
+    assert L.moe_pool_export(ctypes.c_void_p(4096), None, ctypes.byref(off)) == B.MOE_ERR_ARG
+    p = ctypes.c_void_p()
+    assert L.moe_pool_open(None, 0, ctypes.byref(p)) == B.MOE_ERR_ARG
+    assert L.moe_pool_open(h, 0, None) == B.MOE_ERR_ARG
+    assert L.moe_pool_close(None, 0) == B.MOE_ERR_ARG
