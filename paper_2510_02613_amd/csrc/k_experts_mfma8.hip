@@ -482,13 +482,18 @@ size_t mfma8_partial_bytes() { return (size_t)kMaxPartialSets * kPartialFloats *
 
 hipError_t launch_experts_mfma8(const Pass &p0, int which, hipStream_t st)
 {
-    static int cus = 0;
+    // compute units of the CURRENT device (looked up once per device: a process may drive several)
+    static int cus_of[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    int cus = dev >= 0 && dev < 64 ? cus_of[dev] : 0;
     if (cus == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
         cus = n >= kXcds ? n : kXcds;
+        if (dev >= 0 && dev < 64) cus_of[dev] = cus;
     }
     Pass p = p0;
     p.n_cus = cus;

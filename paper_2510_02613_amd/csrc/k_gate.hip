@@ -54,11 +54,11 @@ __device__ int select_token(const Pass &p, int t, float *lg, float *cs, float *g
         for (int e = lane; e < E; e += 64) m = fmaxf(m, lg[e]);
         m = wave_max_f32(m);
         float z = 0.f;
-        for (int e = lane; e < E; e += 64) { float v = expf(lg[e] - m); lg[e] = v; z += v; }
+        for (int e = lane; e < E; e += 64) { float v = __expf(lg[e] - m); lg[e] = v; z += v; }   // hardware exp2: ~1e-7 relative, far inside the 1e-5 tie bar
         z = wave_sum_f32(z);
         for (int e = lane; e < E; e += 64) lg[e] = lg[e] / z;
     } else {
-        for (int e = lane; e < E; e += 64) lg[e] = 1.f / (1.f + expf(-lg[e]));
+        for (int e = lane; e < E; e += 64) lg[e] = __builtin_amdgcn_rcpf(1.f + __expf(-lg[e]));   // hardware exp2 and reciprocal, ~1 ulp each
     }
     for (int e = lane; e < E; e += 64) cs[e] = lg[e] + (p.select_bias ? p.select_bias[e] : 0.f);
     wave_sync();
