@@ -444,3 +444,21 @@ def test_largest_fp32_router_gate_tiling():
     wl = MoEWorkload(name="gate128", tokens=8192, hidden=256, inter=64, n_experts=128, top_k=4, n_slots=9,
                      n_local=8, act_dtype="bf16", router_dtype="f32", gate="softmax", seed=28)
     _full_check(_case(wl), sample=256)
+
+
+def test_many_slots_bookkeeping():
+    """A pool of 1500 slots (the scan over the slots takes several rounds in every bookkeeping kernel), 1024
+    experts of which 900 are resident in scattered slots, 3 shared experts; both bookkeeping paths."""
+    from paper_2510_02613_amd.binding import MOE_FLAG_PERMUTE_UNFUSED
+    wl = MoEWorkload(name="many_slots", tokens=700, hidden=64, inter=8, n_experts=1024, top_k=8, n_slots=1500,
+                     n_local=900, act_dtype="bf16", router_dtype="bf16", gate="softmax", n_shared=3,
+                     shared_range=(13, 650), seed=29)
+    g = np.random.Generator(np.random.PCG64(31))
+    slots = g.permutation(1497)[:900].astype(np.int32)
+    case = _case(wl, expert_map=block_expert_map(1024, 0, 900, slots))
+    out, v, _ = _full_check(case)
+    out2, v2, _ = _full_check(case, flags=MOE_FLAG_PERMUTE_UNFUSED)
+    for key in ("counts", "offsets", "perm", "inv"):
+        np.testing.assert_array_equal(v[key], v2[key])
+    np.testing.assert_array_equal(out, out2)
+    assert (v["counts"] > 0).sum() > 500
