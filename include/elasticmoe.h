@@ -116,7 +116,7 @@ typedef struct {
     const void    *y;         /* [A,H]    act_dtype, expert outputs before combine */
     const int32_t *active_map;/* [E + n_shared] the device copy of the active map, shared slots last
                                * (an entry <= -2 stands for an expert with several copies) */
-    const int32_t *tiles;     /* [n_tiles][4] the M-tile list of the expert kernels: slot, first grouped row, rows, 0 */
+    const int32_t *tiles;     /* [n_tiles][4] the M-tile list of the expert kernels: slot, first grouped row, rows, 1 if the tile is all of its slot's rows else 0 */
     const int32_t *n_tiles;   /* [1] */
 } moe_workspace_view_t;
 

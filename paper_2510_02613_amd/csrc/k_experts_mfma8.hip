@@ -395,7 +395,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     c.wn = c.wave & 3;
     c.wm = c.wave >> 2;
     c.n_tt = (mt.rows + 31) >> 5;                      // token tiles that exist
-    c.stream_w = p.counts[mt.slot] <= kBM;             // the slot's rows are one chunk: nobody else reads these weights
+    c.stream_w = mt.single != 0;                       // the slot's rows are one chunk: nobody else reads these weights (known from the tile itself: no further lookup before the first weight copies)
     c.xlive = c.wave < 4 ? 0 : min(kXPieces, c.n_tt);  // pieces w, w+4, ... < 4*n_tt (8 rows each)
 
     // ---- staging plan ----

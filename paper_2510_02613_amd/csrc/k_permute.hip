@@ -165,7 +165,7 @@ __device__ __forceinline__ void emit_tiles(const Pass &p, int s, int c, int nt, 
             mt.slot = s;
             mt.row_begin = row_off + i * per;
             mt.rows = max(0, min(per, c - i * per));
-            mt.pad = 0;
+            mt.single = nt == 1;
             dst[idx] = mt;
         }
     }

@@ -14,7 +14,7 @@ struct MTile {
     int32_t slot;
     int32_t row_begin;
     int32_t rows;
-    int32_t pad;
+    int32_t single;   // 1 when the tile is all of its slot's rows (nobody else reads the slot's weights in this pass)
 };
 
 // Everything the kernels need to know about one forward pass.  Plain device

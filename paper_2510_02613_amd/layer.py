@@ -253,7 +253,7 @@ class MoELayer:
         A = int(out["offsets"][S])
         out["perm"] = grab(v.perm, 4 * A, np.int32, (A,))
         n_tiles = int(grab(v.n_tiles, 4, np.int32, (1,))[0])
-        out["tiles"] = grab(v.tiles, 16 * n_tiles, np.int32, (n_tiles, 4))   # slot, first grouped row, rows, 0
+        out["tiles"] = grab(v.tiles, 16 * n_tiles, np.int32, (n_tiles, 4))   # slot, first grouped row, rows, single-tile flag
         es = 2 if self.act_dtype == "bf16" else 4
         npdt = np.uint16 if self.act_dtype == "bf16" else np.float32
         out["h"] = grab(v.h, es * A * self.cfg.inter, npdt, (A, self.cfg.inter))

@@ -200,7 +200,9 @@ def check_bookkeeping(case: Case, v: dict, T: int, shared_range):
     # the M-tile list of the expert kernels: every grouped row in exactly one tile of its own slot
     tiles = v["tiles"]
     if A:
-        assert (tiles[:, 2] > 0).all() and (tiles[:, 3] == 0).all()
+        assert (tiles[:, 2] > 0).all()
+        # fourth field: 1 exactly when the tile is all of its slot's rows
+        np.testing.assert_array_equal(tiles[:, 3], (tiles[:, 2] == counts[tiles[:, 0]]).astype(np.int32))
         covered = np.zeros(A, np.int32)
         for s_, r0, n, _ in tiles:
             assert offs[s_] <= r0 and r0 + n <= offs[s_ + 1], "a tile leaves its slot's rows"
