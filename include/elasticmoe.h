@@ -118,6 +118,12 @@ typedef struct {
                                * (an entry <= -2 stands for an expert with several copies) */
     const int32_t *tiles;     /* [n_tiles][4] the M-tile list of the expert kernels: slot, first grouped row, rows, 1 if the tile is all of its slot's rows else 0 */
     const int32_t *n_tiles;   /* [1] */
+    /* Work units of the large-tile expert kernels (NULL when the layer can never run them): per GEMM a header
+     * {rows of 8 workgroups, N-slices per unit, entries, runs per tile} and a list read in rows of 8 -- entry
+     * 8 i + x is the i-th unit of XCD x: {slot, first grouped row, rows (0: a hole), first N-slice << 1 | single}.
+     * Written only by passes that run those kernels. */
+    const int32_t *unit_hdr;  /* [2][4] */
+    const int32_t *units[2];  /* [entries][4] of GEMM-1 and GEMM-2 */
 } moe_workspace_view_t;
 
 /* moe_forward flags */

@@ -49,7 +49,8 @@ class MoEBuffers(ctypes.Structure):
 
 class MoEWorkspaceView(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("topk_ids", "topk_w", "counts", "offsets", "perm", "inv", "h", "y", "active_map", "tiles", "n_tiles")]
+                ("topk_ids", "topk_w", "counts", "offsets", "perm", "inv", "h", "y", "active_map", "tiles", "n_tiles",
+                 "unit_hdr", "units0", "units1")]
 
 
 class MoEError(RuntimeError):

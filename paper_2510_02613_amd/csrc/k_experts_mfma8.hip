@@ -332,31 +332,23 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     const int K = kFirst ? p.H : p.I;
     const int N = kFirst ? p.I : p.H;                  // output columns
     constexpr int BNO = kFirst ? kBN / 2 : kBN;        // output columns per workgroup
-    const int n_ntiles = (N + BNO - 1) / BNO;
 
-    // Work is dealt to the 8 XCDs in UNITS: a chunk of the (size-ordered) tile list with a run of its
-    // N-slices.  Unit u belongs to XCD u % 8 -- largest chunks first on every XCD, loads equal to
-    // within one unit -- and workgroup ids are dealt round-robin to the XCDs by the hardware, so
-    // workgroup b works for XCD b % 8 and takes that XCD's units in order, the N-slices of a unit
-    // on consecutive workgroups (they share the chunk's token rows in that XCD's L2).  A chunk is
-    // one unit when the chunks deal out evenly enough (at most 5 % of an XCD's share idle if they
-    // were all alike); otherwise its N-slices are split into g equal runs, g the smallest divisor
-    // that does -- every extra run of a chunk costs one more XCD a fetch of the chunk's token rows.
-    const int n_chunks = *p.n_tiles;
-    int g = n_ntiles;
-    for (int d = 1; d < n_ntiles; ++d) {
-        const int units = n_chunks * d, dealt = (units + kXcds - 1) / kXcds * kXcds;
-        if (n_ntiles % d == 0 && (dealt - units) * 20 <= units) { g = d; break; }
-    }
-    const int spp = n_ntiles / g;                      // N-slices per unit
+    // Work is dealt to the 8 XCDs in UNITS: a tile (chunk) of the size-ordered list with a run of its
+    // N-slices.  The unit list of this GEMM was written by the bookkeeping kernel in rows of 8 -- entry
+    // 8 i + x is the i-th unit of XCD x, largest tiles first on every XCD, loads equal to within one unit,
+    // the tiles of one slot one behind the other on one XCD -- and workgroup ids are dealt round-robin to
+    // the XCDs by the hardware, so workgroup b works for XCD b % 8 and takes that XCD's units in order,
+    // the N-slices of a unit on consecutive workgroups (they share the tile's token rows in that XCD's L2).
+    const UnitHdr hdr = p.unit_hdr[kFirst ? 0 : 1];
+    const int spp = hdr.spp;                           // N-slices per unit
 
     // The tail of the launch.  Workgroups run in rounds of one per compute unit; with long
     // contractions a launch is only a few rounds deep, and a last round that fills a fraction of the
     // chip costs a whole round.  When the launch allows it (p.k_split), the workgroups of that last
     // round are run separately: each tile's contraction is shared out over n_parts workgroups
     // (phase 1, partial sums to p.partials), which a third launch adds up in K order (phase 2).  The
-    // split is a function of the tile list alone, so all three launches agree on it.
-    const int rows_total = (n_chunks * g + kXcds - 1) / kXcds * spp;   // rows of 8 workgroups, holes of the last unit row included
+    // split is a function of the unit list alone, so all three launches agree on it.
+    const int rows_total = hdr.n_rows;                 // rows of 8 workgroups, holes at the ends of the columns included
     const int rows_round = min(p.n_cus, kMaxPartialSets) / kXcds;
     int tail_rows = 0, n_parts = 1;
     if (p.k_split && rows_total >= rows_round) {
@@ -382,11 +374,11 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     }
     float *tile_sets = kPhase == 0 ? nullptr : p.partials + (size_t)((b - head_blocks) * n_parts) * kPartialFloats;
     const int j = b / kXcds;
-    const int unit = (j / spp) * kXcds + b % kXcds;
-    const int chunk = unit / g;
-    if (chunk >= n_chunks) return;
-    const MTile mt = p.tiles[chunk];
-    const int n0 = ((unit % g) * spp + j % spp) * BNO;
+    const MUnit un = p.units[kFirst ? 0 : 1][(j / spp) * kXcds + b % kXcds];
+    if (un.rows == 0) return;                          // a hole at the end of this XCD's column
+    MTile mt;
+    mt.slot = un.slot; mt.row_begin = un.row_begin; mt.rows = un.rows; mt.single = un.info & 1;
+    const int n0 = ((un.info >> 1) + j % spp) * BNO;
 
     __shared__ __attribute__((aligned(1024))) char ring[kLdsBytes];
     WaveCtx c;
@@ -480,6 +472,13 @@ bool mfma8_supports(const Pass &p)
 
 size_t mfma8_partial_bytes() { return (size_t)kMaxPartialSets * kPartialFloats * sizeof(float); }
 
+int mfma8_n_slices(int H, int I, int which) { return which == 0 ? (I + kBN / 2 - 1) / (kBN / 2) : (H + kBN - 1) / kBN; }
+
+// Rows of 8 workgroups a launch provides (and unit rows x N-slices per unit its unit list has room for):
+// every tile's N-slices, dealt evenly (rounded up to whole units), plus kUnitSlack units per column for columns
+// of unequal length when the tiles of a slot are kept on one XCD.
+int mfma8_grid_rows(int max_tiles, int n_slices) { return (max_tiles * n_slices + kXcds - 1) / kXcds + (kUnitSlack + 1) * n_slices; }
+
 hipError_t launch_experts_mfma8(const Pass &p0, int which, hipStream_t st)
 {
     // compute units of the CURRENT device (looked up once per device: a process may drive several)
@@ -500,8 +499,9 @@ hipError_t launch_experts_mfma8(const Pass &p0, int which, hipStream_t st)
     // sharing out the contraction of the last round's tiles pays when a tile is long: 64 weight steps or more
     const int K = which == 0 ? p.H : p.I;
     p.k_split = p.partials != nullptr && K / kBKW >= 64;
-    const int nt = which == 0 ? (p.I + kBN / 2 - 1) / (kBN / 2) : (p.H + kBN - 1) / kBN;
-    const int grid = (p.max_tiles + kXcds - 1) * nt / kXcds * kXcds + kXcds;   // covers every split of the N-slices into units
+    if (!p.units[0] || !p.unit_hdr) return hipErrorInvalidValue;   // the bookkeeping kernel must have been asked for unit lists
+    const int nt = p.n_slices[which];
+    const int grid = mfma8_grid_rows(p.max_tiles, nt) * kXcds;
     const int round_blocks = (cus < kMaxPartialSets ? cus : kMaxPartialSets) / kXcds * kXcds;
     if (which == 0) {
         hipLaunchKernelGGL((k_expert_gemm_mfma8<true, 0>), dim3(grid), dim3(kThreads), 0, st, p);

@@ -201,6 +201,215 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan_u64(unsigned 
     return base + incl - v;
 }
 
+// Units of one GEMM in list order: the tile at place q of the order, run r -> unit q runs + r (unit u works for
+// XCD u mod 8).  `threads` threads starting at `first` take part.  src: the tiles; order[q]: index in src of the
+// tile at place q (NULL: src is in order already).
+__device__ void deal_units(const Pass &p, const MTile *src, const int32_t *order, int n, int which, int first, int threads)
+{
+    const int t = (int)threadIdx.x - first;
+    const int ns = p.n_slices[which];
+    const int runs = mfma8_runs(n, ns), spp = ns / runs;
+    MUnit *units = p.units[which];
+    const int n_units = min((n * runs + 7) / 8 * 8, p.unit_cap);
+    for (int at = t; at < n * runs && at < p.unit_cap; at += threads) {
+        const int q = at / runs, r = at - q * runs;
+        const MTile mt = src[order ? order[q] : q];
+        MUnit u;
+        u.slot = mt.slot; u.row_begin = mt.row_begin; u.rows = mt.rows;
+        u.info = ((r * spp) << 1) | (mt.single & 1);
+        units[at] = u;
+    }
+    for (int at = n * runs + t; at < n_units; at += threads) {
+        MUnit u;
+        u.slot = 0; u.row_begin = 0; u.rows = 0; u.info = 0;
+        units[at] = u;
+    }
+    if (t == 0) {
+        UnitHdr h;
+        h.n_rows = n_units / 8 * spp; h.spp = spp; h.n_units = n_units; h.runs = runs;
+        p.unit_hdr[which] = h;
+    }
+}
+template <int NT>
+__device__ void deal_units_in_order(const Pass &p, const MTile *src, const int32_t *order, int n)
+{
+    deal_units(p, src, order, n, 0, 0, NT);
+    deal_units(p, src, order, n, 1, 0, NT);
+}
+// exclusive scan of a 64-bit value over one HALF of the block's NT threads (threads [0, NT/2) and [NT/2, NT) scan
+// separately, both halves call it together); scratch: NT/64 entries
+template <int NT>
+__device__ __forceinline__ unsigned long long half_exclusive_scan_u64(unsigned long long v, unsigned long long *scratch, unsigned long long *total)
+{
+    constexpr int HW = NT / 128;                            // wavefronts per half
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = wave / HW;
+    unsigned long long incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) scratch[wave] = incl;
+    __syncthreads();
+    unsigned long long base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < HW; ++w) {
+        const unsigned long long x = scratch[half * HW + w];
+        if (half * HW + w < wave) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+// Units of both GEMMs with the tiles of a slot kept on one XCD (see offsets_and_tiles); all NT threads call it:
+// the first half of them deals GEMM-1's units, the second half GEMM-2's, side by side.
+//   src, order   the tiles and the order (order[q]: index in src of the tile at place q)
+//   gq0[g]       first place of group g of ng (maximal runs of one slot in the order)
+//   tmp          kSortMax ints of LDS (the pieces, a half per GEMM), scratch: the scans'
+// A GEMM falls back to the plain deal (unit q runs + r to XCD u mod 8) when its pieces do not fit tmp or a column
+// would outgrow what the launch provides.
+template <int NT>
+__device__ void deal_units_grouped(const Pass &p, const MTile *src, const int32_t *order, const int32_t *gq0,
+                                   int ng, int n, int32_t *tmp_all, unsigned long long *scratch)
+{
+    constexpr int HT = NT / 2;
+    __shared__ int32_t colF_all[2][8];   // units at the head of every column that belong to pieces
+    const int which = (int)threadIdx.x / HT, t = (int)threadIdx.x % HT;
+    int32_t *tmp = tmp_all + which * (kSortMax / 2);
+    int32_t *colF = colF_all[which];
+    const int ns = p.n_slices[which];
+    const int runs = mfma8_runs(n, ns), spp = ns / runs;
+    const int total = n * runs;
+    const int target = (total + 7) / 8, limit = target + kUnitSlack;
+    const int pm = max(2, target / 2);                     // largest piece
+    MUnit *units = p.units[which];
+    if (t < 8) colF[t] = 0;
+    const bool ok = total <= kSortMax / 2 && runs <= 64;
+    // pieces and single tiles per group -> each group's start in the two numberings (one scan, two counters)
+    auto shape = [&](int g, int &m, int &np, int &singles) {
+        m = (g + 1 < ng ? gq0[g + 1] : n) - gq0[g];
+        np = 0; singles = 0;
+        if (m == 1) { singles = 1; }
+        else {
+            np = (m + pm - 1) / pm;
+            if (m - (np - 1) * pm == 1) { --np; singles = 1; }   // a last piece of one tile is a single tile
+        }
+    };
+    unsigned long long carry = 0;
+    for (int g0 = 0; g0 < ng; g0 += HT) {
+        const int g = g0 + t;
+        int m = 0, np = 0, singles = 0;
+        if (g < ng) shape(g, m, np, singles);
+        unsigned long long tot;
+        const unsigned long long at = carry + half_exclusive_scan_u64<NT>(((unsigned long long)(np * runs) << 32) | (unsigned)(singles * runs), scratch, &tot);
+        if (g < ng && ok) {
+            const int k0 = (int)(at >> 32);
+            for (int pi = 0; pi < np; ++pi) {
+                const int size = min(pm, m - pi * pm);
+                for (int r = 0; r < runs; ++r)              // first place in the order (11 bits) | tiles (11) | run (6)
+                    tmp[k0 + pi * runs + r] = (gq0[g] + pi * pm) | (size << 11) | (r << 22);
+            }
+            // the group's single tile starts at this number among the single units (kept for the second pass)
+        }
+        carry += tot;
+    }
+    const int P = (int)(carry >> 32), R = (int)(carry & 0xffffffffu);
+    __syncthreads();
+    // piece k sits in column k mod 8 behind the earlier pieces of that column
+    if (ok) {
+        for (int k = t; k < P; k += HT) {
+            if (k + 8 >= P) {                                // the last piece of its column knows the column's length
+                int at = 0;
+                for (int j = k & 7; j < k; j += 8) at += (tmp[j] >> 11) & 0x7ff;
+                colF[k & 7] = at + ((tmp[k] >> 11) & 0x7ff);
+            }
+        }
+    }
+    __syncthreads();
+    int F[8], Fmax = 0;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) { F[x] = colF[x]; Fmax = max(Fmax, F[x]); }
+    const bool grouped = ok && Fmax <= limit;               // uniform over the half
+    // level of single unit i: the largest l with C(l) <= i, C(l) = sum over columns of max(0, l - F[x]) = single units below level l
+    auto below = [&](int l) { int c = 0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) c += max(0, l - F[x]);
+        return c; };
+    auto level_of = [&](int i) {
+        int lo = 0, hi = Fmax + (R + 7) / 8 + 1;               // C(lo) = 0 <= i < C(hi)
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (below(mid) <= i) lo = mid; else hi = mid; }
+        return lo; };
+    auto put = [&](int row, int x, const MTile &tl, int r) {
+        MUnit u;
+        u.slot = tl.slot; u.row_begin = tl.row_begin; u.rows = tl.rows;
+        u.info = ((r * spp) << 1) | (tl.single & 1);
+        units[(size_t)row * 8 + x] = u;
+    };
+    if (grouped) {
+        for (int k = t; k < P; k += HT) {
+            int at = 0;
+            for (int j = k & 7; j < k; j += 8) at += (tmp[j] >> 11) & 0x7ff;
+            const int w = tmp[k], q = w & 0x7ff, size = (w >> 11) & 0x7ff, r = (w >> 22) & 0x3f;
+            for (int i = 0; i < size; ++i) put(at + i, k & 7, src[order[q + i]], r);
+        }
+        // column x ends where its single units end: one per level from F[x] to the last level, which only the
+        // first `last_n` of the columns that reach it take part in
+        const int l_last = R ? level_of(R - 1) : -1;
+        const int last_n = R ? R - below(l_last) : 0;
+        const int rows_used = R ? max(Fmax, l_last + 1) : Fmax;
+        if (t < 8) {
+            int fill = F[0];
+#pragma unroll
+            for (int x = 1; x < 8; ++x) if (t == x) fill = F[x];
+            if (R && fill <= l_last) {
+                int before = 0;
+#pragma unroll
+                for (int y = 0; y < 8; ++y) before += (y < t && F[y] <= l_last);
+                fill = before < last_n ? l_last + 1 : l_last;
+            }
+            for (int row = fill; row < rows_used; ++row) {   // holes
+                MUnit u;
+                u.slot = 0; u.row_begin = 0; u.rows = 0; u.info = 0;
+                units[(size_t)row * 8 + t] = u;
+            }
+        }
+        if (t == 0) {
+            UnitHdr h;
+            h.n_rows = rows_used * spp; h.spp = spp; h.n_units = rows_used * 8; h.runs = runs;
+            p.unit_hdr[which] = h;
+        }
+    }
+    // single units, numbered group by group in the order (a group has at most one single tile), run by run
+    unsigned long long carry2 = 0;
+    for (int g0 = 0; g0 < ng; g0 += HT) {
+        const int g = g0 + t;
+        int m = 0, np = 0, has = 0;
+        if (g < ng) shape(g, m, np, has);
+        unsigned long long tot;
+        const int i0 = (int)(carry2 + half_exclusive_scan_u64<NT>((unsigned long long)(has * runs), scratch, &tot));
+        if (has && grouped) {
+            const MTile tl = src[order[gq0[g] + m - 1]];      // the group's last tile
+            for (int r = 0; r < runs; ++r) {
+                const int i = i0 + r, l = level_of(i);
+                const int rank = i - below(l);
+                int x = 0;
+#pragma unroll
+                for (int xx = 7; xx >= 0; --xx) {            // the rank-th column (ascending) that is no longer than l
+                    int before = 0;
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) before += (y < xx && F[y] <= l);
+                    if (F[xx] <= l && before == rank) x = xx;
+                }
+                put(l, x, tl, r);
+            }
+        }
+        carry2 += tot;
+    }
+    if (!grouped) deal_units(p, src, order, n, which, which * HT, HT);
+}
+
 // Rows per slot, row offsets and the M-tile list, written by one workgroup of NT threads from
 //   cnt[s]   (LDS) rows per slot
 //   fkey[s]  (LDS) first assignment of the slot's group, INT_MAX without rows
@@ -219,8 +428,11 @@ __device__ void offsets_and_tiles(const Pass &p, int tile_rows, bool staging, co
     __shared__ unsigned long long scratch[NT / 64];
     __shared__ MTile staged[kSortMax];
     __shared__ unsigned long long skey[kSortMax];
-    __shared__ int32_t scratch_pos[NT];      // places of the tiles of a short list (fewer than NT tiles)
+    __shared__ int32_t tpos[kSortMax];       // a tile's place in the order
+    __shared__ int32_t any_multi;            // some slot has several tiles
     const int tid = threadIdx.x;
+    if (tid == 0) any_multi = 0;
+    __syncthreads();
     const int S = p.S;
     // one scan over the slots for both offsets: rows in the high half, tiles in the low half
     unsigned long long carry = 0;
@@ -235,6 +447,7 @@ __device__ void offsets_and_tiles(const Pass &p, int tile_rows, bool staging, co
             p.counts[s] = c;
             p.offs[s] = row_off;
             emit_tiles(p, s, c, nt, row_off, tile_off, tile_rows, staging ? staged : p.tiles);
+            if (nt > 1) any_multi = 1;
             if (staging) {
                 const int gran = tile_rows < 32 ? tile_rows : 32;
                 const int per = nt ? min(tile_rows, ((c + nt - 1) / nt + gran - 1) / gran * gran) : 0;
@@ -253,48 +466,75 @@ __device__ void offsets_and_tiles(const Pass &p, int tile_rows, bool staging, co
         p.offs[S] = n_rows;
         *p.n_tiles = n;
     }
-    if (!staging) return;
     __syncthreads();
-    // a short list is shared out over all threads: `parts` threads per tile, each counting a range of the others
-    const int parts = n > 0 && n < NT ? NT / n : 1;
-    if (parts > 1) {
-        int32_t *pos = (int32_t *)scratch_pos;
-        for (int i = tid; i < n; i += NT) pos[i] = 0;
-        __syncthreads();
-        const int i = tid % n, part = tid / n;
-        if (part < parts) {
-            const int per = (n + parts - 1) / parts, j0 = part * per, j1 = min(n, j0 + per);
-            const unsigned long long mine = skey[i];
-            int cntl = 0;
-            int j = j0;
-            for (; j + 8 <= j1; j += 8) {
-                unsigned long long k[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) k[u] = skey[j + u];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) cntl += k[u] < mine;
-            }
-            for (; j < j1; ++j) cntl += skey[j] < mine;
-            atomicAdd(&pos[i], cntl);
+    const bool multi = any_multi != 0;
+    if (!staging) {
+        if (p.units[0]) {   // a list too long to order: units straight from the slot-ordered list in global memory
+            __threadfence();
+            __syncthreads();
+            deal_units_in_order<NT>(p, p.tiles, nullptr, n);
         }
-        __syncthreads();
-        for (int i2 = tid; i2 < n; i2 += NT) p.tiles[pos[i2]] = staged[i2];
         return;
     }
-    for (int i = tid; i < n; i += NT) {
+    __syncthreads();
+    // a tile's place in the order: a short list is shared out over all threads (`parts` threads per tile,
+    // each counting a range of the others)
+    for (int i = tid; i < n; i += NT) tpos[i] = 0;
+    __syncthreads();
+    const int parts = n > 0 && n < NT ? NT / n : 1;
+    for (int w = tid; w < n * parts; w += NT) {
+        const int i = w % n, part = w / n;
+        const int per = (n + parts - 1) / parts, j0 = part * per, j1 = min(n, j0 + per);
         const unsigned long long mine = skey[i];
-        int pos = 0;
-        int j = 0;
-        for (; j + 8 <= n; j += 8) {
+        int cntl = 0;
+        int j = j0;
+        for (; j + 8 <= j1; j += 8) {
             unsigned long long k[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) k[u] = skey[j + u];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) pos += k[u] < mine;
+            for (int u = 0; u < 8; ++u) cntl += k[u] < mine;
         }
-        for (; j < n; ++j) pos += skey[j] < mine;
-        p.tiles[pos] = staged[i];
+        for (; j < j1; ++j) cntl += skey[j] < mine;
+        atomicAdd(&tpos[i], cntl);
     }
+    __syncthreads();
+    for (int i = tid; i < n; i += NT) p.tiles[tpos[i]] = staged[i];
+    if (!p.units[0]) return;
+    // ---- work units of the large-tile GEMMs ----
+    int32_t *inv = (int32_t *)skey;                 // order -> staged index (the keys are no longer needed)
+    __syncthreads();
+    for (int i = tid; i < n; i += NT) inv[tpos[i]] = i;
+    __syncthreads();
+    // Keeping a slot's tiles on one XCD costs this workgroup -- the longest of the launch -- several more scans;
+    // it pays when a tile's weights are tens of megabytes (measured: hidden x intermediate of 7168 x 2048 gains
+    // 5 % in GEMM-2 and 5 % of the fetched bytes, 2048 x 768 gains nothing)
+    if (!multi || (long long)p.H * p.I < (4ll << 20)) {
+        deal_units_in_order<NT>(p, staged, inv, n);
+        return;
+    }
+    // Some slot has several tiles: their weights are worth fetching once.  The tiles of one slot (of one size
+    // class: they sit next to each other in the order) form a group; a group's units go to ONE XCD, one behind
+    // the other at the head of that XCD's column, so that they run at the same time and the later ones find the
+    // slot's weights in that XCD's L2.  Everything is closed form, no thread walks the list: groups are cut into
+    // pieces of at most half a column, piece k goes to XCD k mod 8, and the single tiles then fill the columns up
+    // level by level (a tile goes to the shortest columns first), in size order.
+    int32_t *gq0 = inv + kSortMax;                  // group -> its first place in the order
+    __shared__ int32_t n_groups;
+    {   // groups: maximal runs of one slot in the order; compacted by a scan of the run starts
+        int carry_g = 0;
+        for (int q0 = 0; q0 < n; q0 += NT) {
+            const int q = q0 + tid;
+            const int start = q < n && (q == 0 || staged[inv[q]].slot != staged[inv[q - 1]].slot) ? 1 : 0;
+            unsigned long long tot;
+            const int at = carry_g + (int)block_exclusive_scan_u64<NT>((unsigned long long)start, scratch, &tot);
+            if (start) gq0[at] = q;
+            carry_g += (int)tot;
+        }
+        if (tid == 0) n_groups = carry_g;
+    }
+    __syncthreads();
+    deal_units_grouped<NT>(p, staged, inv, gq0, n_groups, n, tpos, scratch);
 }
 
 // sort_tiles != 0: a size-ordered tile list (lists longer than kSortMax stay in slot order).

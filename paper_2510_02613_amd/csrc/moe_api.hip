@@ -51,7 +51,8 @@ constexpr int kMinTileRows = 16;  // smallest M-tile any expert kernel uses: siz
 
 // Offsets of every intermediate inside the workspace.
 struct Layout {
-    size_t map, logits, ids, w, slot_rank, blk_hist, blk_cnt, counts, offs, perm, inv, tiles, n_tiles, h, y, partials, total;
+    size_t map, logits, ids, w, slot_rank, blk_hist, blk_cnt, counts, offs, perm, inv, tiles, n_tiles, units[2], unit_hdr, h, y, partials, total;
+    size_t unit_cap;
     bool has_partials;
 };
 
@@ -113,6 +114,16 @@ Layout make_layout(const moe_config_t &c)
     L.inv = take(4 * A);
     L.tiles = take(sizeof(MTile) * max_tiles);
     L.n_tiles = take(4);
+    // unit lists of the large-tile GEMMs (layers they can serve): one entry per (tile, run of N-slices), in rows of 8
+    L.unit_cap = 0;
+    if (c.act_dtype == MOE_BF16 && c.hidden % 64 == 0 && c.inter % 64 == 0 && (long long)A >= 48ll * S) {
+        const size_t big_tiles = (A + mfma8_tile_rows() - 1) / mfma8_tile_rows() + S;
+        const int ns0 = mfma8_n_slices(c.hidden, c.inter, 0), ns1 = mfma8_n_slices(c.hidden, c.inter, 1);
+        L.unit_cap = 8 * (size_t)mfma8_grid_rows((int)big_tiles, ns0 > ns1 ? ns0 : ns1);
+    }
+    L.units[0] = take(sizeof(MUnit) * L.unit_cap);
+    L.units[1] = take(sizeof(MUnit) * L.unit_cap);
+    L.unit_hdr = take(L.unit_cap ? 2 * sizeof(UnitHdr) : 0);
     L.h = take(esize(c.act_dtype) * A * c.inter);
     L.y = take(esize(c.act_dtype) * A * c.hidden);
     // partial sums of split tiles: only layers whose large-tile GEMMs can have contractions long enough to split
@@ -429,6 +440,9 @@ moe_status_t moe_workspace_view(const moe_layer_t *l, moe_workspace_view_t *v)
     v->active_map = (const int32_t *)(ws + l->lay.map);
     v->tiles = (const int32_t *)(ws + l->lay.tiles);
     v->n_tiles = (const int32_t *)(ws + l->lay.n_tiles);
+    v->unit_hdr = l->lay.unit_cap ? (const int32_t *)(ws + l->lay.unit_hdr) : nullptr;
+    v->units[0] = l->lay.unit_cap ? (const int32_t *)(ws + l->lay.units[0]) : nullptr;
+    v->units[1] = l->lay.unit_cap ? (const int32_t *)(ws + l->lay.units[1]) : nullptr;
     return MOE_OK;
 }
 
@@ -476,6 +490,8 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     p.inv = (int32_t *)(ws + l->lay.inv);
     p.tiles = (MTile *)(ws + l->lay.tiles);
     p.n_tiles = (int32_t *)(ws + l->lay.n_tiles);
+    p.units[0] = p.units[1] = nullptr;
+    p.unit_hdr = nullptr;
     p.h = ws + l->lay.h;
     p.y = ws + l->lay.y;
     p.partials = l->lay.has_partials ? (float *)(ws + l->lay.partials) : nullptr;
@@ -491,6 +507,14 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     const bool tiny = mfma && !big && (long long)T * p.k <= 4ll * p.E && shared_end - shared_begin <= 2 * decode_tile_rows();
     const int tile_rows = big ? mfma8_tile_rows() : tiny ? decode_tile_rows() : mfma ? mfma_tile_rows() : kGenericTileRows;
     p.max_tiles = (int)(((long long)T * p.kk + tile_rows - 1) / tile_rows) + p.S;
+    if (big) {   // the tile-list workgroup also deals the tiles' N-slices to the XCDs, per GEMM
+        p.units[0] = (MUnit *)(ws + l->lay.units[0]);
+        p.units[1] = (MUnit *)(ws + l->lay.units[1]);
+        p.unit_hdr = (UnitHdr *)(ws + l->lay.unit_hdr);
+        p.unit_cap = (int32_t)l->lay.unit_cap;
+        p.n_slices[0] = mfma8_n_slices(p.H, p.I, 0);
+        p.n_slices[1] = mfma8_n_slices(p.H, p.I, 1);
+    }
 
     // optional phase events (benchmarks): event j is recorded before phase j, the last one after the pass
     hipEvent_t *ev = l->prof_on && l->prof_seen++ % l->prof_every == 0 ? l->ev[l->prof_count % kProfRing] : nullptr;

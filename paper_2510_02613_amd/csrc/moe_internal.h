@@ -17,6 +17,35 @@ struct MTile {
     int32_t single;   // 1 when the tile is all of its slot's rows (nobody else reads the slot's weights in this pass)
 };
 
+// One work unit of the large-tile GEMMs: an M-tile with a run of its N-slices.  The unit list of a GEMM is
+// read as rows of 8: entry 8 i + x is the i-th unit of XCD x (workgroup b serves XCD b mod 8), so which
+// column a unit sits in decides where it runs; rows == 0 marks a hole at the end of a column.
+struct MUnit {
+    int32_t slot;
+    int32_t row_begin;
+    int32_t rows;
+    int32_t info;     // first N-slice of the run << 1 | the tile's single flag
+};
+struct UnitHdr {
+    int32_t n_rows;   // rows of 8 workgroups the launch has to run: unit rows x spp
+    int32_t spp;      // N-slices per unit
+    int32_t n_units;  // entries of the list, holes included (a multiple of 8)
+    int32_t runs;     // runs a tile's N-slices are split into
+};
+
+constexpr int kUnitSlack = 2;   // units by which an XCD's column of the unit list may exceed an even deal
+
+// Runs a tile's N-slices are split into so that the units deal out evenly to the 8 XCDs: the smallest
+// divisor d of n_slices with at most 5 % of an XCD's share idle if all units were alike, else n_slices.
+__host__ __device__ inline int mfma8_runs(int n_chunks, int n_slices)
+{
+    for (int d = 1; d < n_slices; ++d) {
+        const int units = n_chunks * d, dealt = (units + 7) / 8 * 8;
+        if (n_slices % d == 0 && (dealt - units) * 20 <= units) return d;
+    }
+    return n_slices;
+}
+
 // Everything the kernels need to know about one forward pass.  Plain device
 // pointers into caller-owned memory (x/out/weights) and the caller's workspace.
 struct Pass {
@@ -48,6 +77,10 @@ struct Pass {
     int32_t *inv;        // [T,kk]
     MTile *tiles;        // [max_tiles]
     int32_t *n_tiles;    // [1]
+    MUnit *units[2];     // large-tile GEMMs only: the unit lists of GEMM-1 and GEMM-2, unit_cap entries each (else NULL)
+    UnitHdr *unit_hdr;   // [2]
+    int32_t unit_cap;
+    int32_t n_slices[2]; // N-slices of a tile in GEMM-1 and GEMM-2
     void *h;             // [A,I]
     void *y;             // [A,H]
     int32_t max_tiles;
@@ -80,6 +113,8 @@ int mfma_tile_rows();
 hipError_t launch_experts_mfma8(const Pass &p, int which, hipStream_t st);
 int mfma8_tile_rows();
 bool mfma8_supports(const Pass &p);
+int mfma8_n_slices(int H, int I, int which);   // N-slices of a tile in GEMM-1 (which = 0) or GEMM-2
+int mfma8_grid_rows(int max_tiles, int n_slices);   // rows of 8 workgroups a launch provides
 size_t mfma8_partial_bytes();   // workspace for the partial sums of tiles whose contraction is shared out
 hipError_t launch_ceiling_mfma(int blocks, int iters, int random_operands, float *sink, hipStream_t st);
 double ceiling_mfma_flops(int blocks, int iters);

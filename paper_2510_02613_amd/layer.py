@@ -254,6 +254,13 @@ class MoELayer:
         out["perm"] = grab(v.perm, 4 * A, np.int32, (A,))
         n_tiles = int(grab(v.n_tiles, 4, np.int32, (1,))[0])
         out["tiles"] = grab(v.tiles, 16 * n_tiles, np.int32, (n_tiles, 4))   # slot, first grouped row, rows, single-tile flag
+        # unit lists of the large-tile kernels (meaningful after a pass that ran them)
+        out["unit_hdr"], out["units"] = None, None
+        if v.unit_hdr:
+            hdr = grab(v.unit_hdr, 32, np.int32, (2, 4))
+            out["unit_hdr"] = hdr
+            cap = (v.units1 - v.units0) // 16
+            out["units"] = [grab(ptr, 16 * int(min(max(hdr[w, 2], 0), cap)), np.int32, (-1, 4)) for w, ptr in ((0, v.units0), (1, v.units1))]
         es = 2 if self.act_dtype == "bf16" else 4
         npdt = np.uint16 if self.act_dtype == "bf16" else np.float32
         out["h"] = grab(v.h, es * A * self.cfg.inter, npdt, (A, self.cfg.inter))

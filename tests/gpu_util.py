@@ -170,8 +170,15 @@ def check_routing(case: Case, gpu_ids: np.ndarray, gpu_w: np.ndarray):
     return gpu_ids, int((flags != 0).sum()), flips
 
 
-def check_bookkeeping(case: Case, v: dict, T: int, shared_range):
-    """counts / offsets / perm / inv against their definitions, from the GPU's own ids."""
+def ran_large_tiles(wl, T, flags=0):
+    """Did a pass of T tokens run the large-tile expert kernels (the host's rule, from shapes alone)?"""
+    return (wl.act_dtype == "bf16" and wl.hidden % 64 == 0 and wl.inter % 64 == 0 and not (flags & 3)
+            and T * (wl.top_k + wl.n_shared) >= 48 * wl.n_slots)
+
+
+def check_bookkeeping(case: Case, v: dict, T: int, shared_range, flags=0):
+    """counts / offsets / perm / inv against their definitions, from the GPU's own ids; the tile list; and,
+    after a pass on the large-tile kernels, their work-unit lists."""
     wl = case.wl
     k, kk, S = wl.top_k, wl.top_k + wl.n_shared, wl.n_slots
     ids = v["topk_ids"]
@@ -210,6 +217,51 @@ def check_bookkeeping(case: Case, v: dict, T: int, shared_range):
         assert (covered == 1).all(), "tiles do not partition the grouped rows"
     else:
         assert len(tiles) == 0
+    if A and ran_large_tiles(wl, T, flags):
+        check_units(case, v)
+
+
+def check_units(case: Case, v: dict):
+    """The work-unit lists of the large-tile kernels (call after a pass that ran them): per GEMM, every N-slice
+    of every tile is in exactly one unit, holes only at the ends of the eight columns, columns differ by at most
+    a few units, and the tiles of a slot that sit together in the tile list share a column when the pass has
+    such groups.  Returns, per GEMM, the share of the avoidable weight fetches (tiles - 1 per multi-tile slot and
+    size) that the columns avoid."""
+    wl = case.wl
+    tiles, hdr, lists = v["tiles"], v["unit_hdr"], v["units"]
+    n_slices = ((wl.inter + 127) // 128, (wl.hidden + 255) // 256)
+    shares = []
+    for w in range(2):
+        n_rows, spp, n_units, runs = (int(x) for x in hdr[w])
+        u = lists[w]
+        assert len(u) == n_units and n_units % 8 == 0 and n_rows == n_units // 8 * spp and spp * runs == n_slices[w]
+        live = u[:, 2] > 0
+        cols = np.arange(n_units) % 8
+        for x in range(8):                                   # a column's holes are all at its end
+            lx = live[cols == x]
+            assert not (np.diff(lx.astype(np.int8)) > 0).any(), "a hole inside a column"
+        fills = np.array([live[cols == x].sum() for x in range(8)])
+        assert fills.max() - fills.min() <= 3 or len(tiles) * runs < 16, fills
+        seen = {}
+        for slot, r0, rows, info in u[live]:
+            s0 = info >> 1
+            assert s0 % spp == 0 and s0 + spp <= n_slices[w]
+            seen[(int(slot), int(r0), int(rows), int(info & 1), int(s0))] = seen.get((int(slot), int(r0), int(rows), int(info & 1), int(s0)), 0) + 1
+        want = {(int(s_), int(r0), int(n), int(f), r * spp) for s_, r0, n, f in tiles for r in range(runs)}
+        assert set(seen) == want and all(c == 1 for c in seen.values()), "units do not cover every (tile, run) exactly once"
+        # co-location: tiles of one slot and one size class (32-row tiles) in one column, run by run
+        groups = {}
+        for i in np.nonzero(live)[0]:
+            slot, r0, rows, info = u[i]
+            groups.setdefault((int(slot), (int(rows) + 31) // 32, int(info >> 1)), set()).add(int(cols[i]))
+        sizes = {}
+        for slot, r0, rows, info in u[live]:
+            sizes[(int(slot), (int(rows) + 31) // 32, int(info >> 1))] = sizes.get((int(slot), (int(rows) + 31) // 32, int(info >> 1)), 0) + 1
+        multi = [k for k, c in sizes.items() if c > 1]
+        # of the weight fetches that sharing a column can save (tiles - 1 per group), the share that is saved
+        # (tiles - columns used); groups larger than half a column are cut on purpose
+        shares.append(sum(sizes[k] - len(groups[k]) for k in multi) / sum(sizes[k] - 1 for k in multi) if multi else None)
+    return shares
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:

@@ -44,7 +44,7 @@ def _full_check(case, flags=0, sample=None, T=None, shared_range=None, report=No
         grade_ids, n_flag, flips = check_routing(case, v["topk_ids"], v["topk_w"])
     else:
         grade_ids, n_flag, flips = None, 0, 0
-    check_bookkeeping(case, v, T, sr)
+    check_bookkeeping(case, v, T, sr, flags)
     tokens = None if T == wl.tokens else np.arange(T, dtype=np.int32)
     if isinstance(sample, tuple):
         tokens = _tile_sample(v, sample[1], sample[2], T, 1234 + wl.seed)
@@ -462,3 +462,31 @@ def test_many_slots_bookkeeping():
         np.testing.assert_array_equal(v[key], v2[key])
     np.testing.assert_array_equal(out, out2)
     assert (v["counts"] > 0).sum() > 500
+
+
+def test_tiles_of_a_slot_share_an_xcd():
+    """Zipf-skewed routing on the large-tile kernels: hot experts have many tiles; the unit lists keep the tiles
+    of a slot (of one size) in one column, i.e. on one XCD, for nearly all of them (a group larger than half a
+    column is cut), and the lists still cover every tile and N-slice once (checked by check_bookkeeping)."""
+    from gpu_util import check_units
+    wl = MoEWorkload(name="colocate", tokens=6000, **{**SMALL, "inter": 1024, "hidden": 4096, "n_experts": 32, "n_slots": 32,
+                                                     "n_local": 32, "zipf_s": 1.2, "seed": 30})
+    case = _case(wl)
+    _, v, _ = _full_check(case)
+    shares = check_units(case, v)
+    assert (v["counts"] > 640).sum() >= 3            # several slots with three or more tiles
+    assert all(s is not None and s >= 0.7 for s in shares), shares
+
+
+def test_shared_expert_tiles_share_an_xcd_on_the_dsv3_shape_small():
+    """One shared expert over 1200 tokens beside single-tile experts (the shape of the DeepSeek-V3-style rank, scaled
+    down): the shared slot's four tiles sit in one column of each unit list."""
+    from gpu_util import check_units
+    wl = MoEWorkload(name="colocate_shared", tokens=4800, hidden=4096, inter=1024, n_experts=128, top_k=8, n_slots=17,
+                     n_local=16, act_dtype="bf16", router_dtype="bf16", gate="sigmoid_group", n_group=8, topk_group=4,
+                     routed_scale=2.5, n_shared=1, shared_range=(0, 1200), seed=31)
+    case = _case(wl)
+    _, v, _ = _full_check(case)
+    assert v["counts"][16] == 1200 and (v["tiles"][:, 0] == 16).sum() == 4
+    shares = check_units(case, v)
+    assert shares == [1.0, 1.0], shares

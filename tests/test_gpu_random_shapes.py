@@ -133,7 +133,7 @@ def _check(wl, emap, local):
     from paper_2510_02613_amd.binding import MOE_FLAG_PERMUTE_UNFUSED
     out2 = case.run(flags=MOE_FLAG_PERMUTE_UNFUSED)
     v2 = case.layer.view(wl.tokens)
-    check_bookkeeping(case, v2, wl.tokens, wl.shared_range)
+    check_bookkeeping(case, v2, wl.tokens, wl.shared_range, MOE_FLAG_PERMUTE_UNFUSED)
     for key in ("topk_ids", "counts", "offsets", "perm", "inv"):
         np.testing.assert_array_equal(v[key], v2[key])
     np.testing.assert_array_equal(out, out2)
