@@ -336,9 +336,20 @@ moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void
  *   moe_vpool_unmap       takes the page from under a slot; the page keeps its contents.
  *   moe_vpool_page_free   releases an unmapped page.       moe_vpool_page_of  page under a slot, or -1.
  *   moe_vpool_destroy     unmaps and releases everything and frees the address range.
+ *   moe_vpool_slot_bytes / moe_vpool_slots   what the pool was created with (0 for NULL).
  * These are the only calls of the library that own device memory.  Mapping calls are host
  * operations, not stream ordered: unmap a slot only when no kernel that can read it is in
  * flight, and never let an expert map name a slot that has no page (reading it faults).
+ *
+ * moe_layer_bind_vpools tells a layer which pools lie under its w13 and w2 (either may be NULL:
+ * that buffer is plain memory); each pool must start at the layer's buffer, have the layer's slot
+ * size and at least its slots (MOE_ERR_ARG otherwise).  From then on the host refuses, with
+ * MOE_ERR_MAP and before anything is enqueued, what would make a kernel touch a slot without a
+ * page: a placement (moe_set_expert_map / moe_set_expert_replicas) that names one, a forward while
+ * the placement in force names one (a page unmapped after the switch), a moe_load_expert into
+ * one; binding itself fails that way when the placement in force is not readable.  Pages under
+ * slots the placement does not name may come and go freely.  A replay of a captured graph runs
+ * no host check.  Destroying a pool unbinds it from its layers; destroying a layer unbinds it.
  */
 moe_status_t moe_vpool_create(size_t slot_bytes, int32_t n_vslots, moe_vpool_t **out);
 void *moe_vpool_base(const moe_vpool_t *pool);
@@ -347,7 +358,10 @@ moe_status_t moe_vpool_page_free(moe_vpool_t *pool, int32_t page);
 moe_status_t moe_vpool_map(moe_vpool_t *pool, int32_t vslot, int32_t page);
 moe_status_t moe_vpool_unmap(moe_vpool_t *pool, int32_t vslot);
 int32_t moe_vpool_page_of(const moe_vpool_t *pool, int32_t vslot);
+size_t moe_vpool_slot_bytes(const moe_vpool_t *pool);
+int32_t moe_vpool_slots(const moe_vpool_t *pool);
 moe_status_t moe_vpool_destroy(moe_vpool_t *pool);
+moe_status_t moe_layer_bind_vpools(moe_layer_t *layer, moe_vpool_t *w13_pool, moe_vpool_t *w2_pool);
 
 /*
  * Zero-copy attach of a weight pool from another process (paper: the zero-copy primitive, Sec. 4.6; its

@@ -25,7 +25,8 @@ EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe
            "moe_workspace_view", "moe_layer_destroy", "moe_last_error", "moe_profile_enable",
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
            "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
-           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_forward_static",
+           "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_vpool_slot_bytes",
+           "moe_vpool_slots", "moe_layer_bind_vpools", "moe_forward_static",
            "moe_pool_export", "moe_pool_open", "moe_pool_close")
 MOE_IPC_HANDLE_BYTES = 64
 MOE_STATIC_SCRATCH_BYTES = 32 << 20
@@ -111,6 +112,12 @@ def lib() -> ctypes.CDLL:
         L.moe_vpool_page_of.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.moe_vpool_destroy.restype = ctypes.c_int
         L.moe_vpool_destroy.argtypes = [ctypes.c_void_p]
+        L.moe_vpool_slot_bytes.restype = ctypes.c_size_t
+        L.moe_vpool_slot_bytes.argtypes = [ctypes.c_void_p]
+        L.moe_vpool_slots.restype = ctypes.c_int32
+        L.moe_vpool_slots.argtypes = [ctypes.c_void_p]
+        L.moe_layer_bind_vpools.restype = ctypes.c_int
+        L.moe_layer_bind_vpools.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.moe_pool_export.restype = ctypes.c_int
         L.moe_pool_export.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.POINTER(ctypes.c_size_t)]
         L.moe_pool_open.restype = ctypes.c_int
@@ -243,6 +250,19 @@ def moe_vpool_page_of(pool, vslot: int) -> int:
 
 def moe_vpool_destroy(pool) -> None:
     _check(lib().moe_vpool_destroy(pool))
+
+
+def moe_vpool_slot_bytes(pool) -> int:
+    return int(lib().moe_vpool_slot_bytes(pool))
+
+
+def moe_vpool_slots(pool) -> int:
+    return int(lib().moe_vpool_slots(pool))
+
+
+def moe_layer_bind_vpools(layer, w13_pool, w2_pool) -> None:
+    """Either pool may be None (that buffer is plain memory)."""
+    _check(lib().moe_layer_bind_vpools(layer, w13_pool, w2_pool))
 
 
 def moe_pool_export(dev_ptr: int):

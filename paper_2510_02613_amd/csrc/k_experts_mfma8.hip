@@ -125,6 +125,14 @@ __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, u
 // complete in order.
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
+    // Timing-only builds (results are garbage): leave out the weight copies, the token copies or (below) the
+    // multiply, to time what is left.  Off unless the build defines the macro.
+#ifdef EMOE_TIMING_NO_W
+    if (c.wave < 4) return;
+#endif
+#ifdef EMOE_TIMING_NO_X
+    if (c.wave >= 4) return;
+#endif
     if (c.wave < 4) {
         const uint16_t *b = c.wbase + k0;
         if (c.stream_w) {
@@ -169,6 +177,10 @@ __device__ __forceinline__ void wait_loads()
 template <int NTC, typename Mid>
 __device__ __forceinline__ void multiply_stage(const WaveCtx &c, const char *Ws, const char *Xs, f32x16 (&acc)[kWT][kTC], Mid mid)
 {
+#ifdef EMOE_TIMING_NO_MUL
+    mid();
+    return;
+#endif
     if constexpr (NTC > 0) {
         constexpr int KS = kBK / 16, STEPS = KS * NTC, D = 2;
         bf16x8 wf[2][kWT], xf[D + 1];

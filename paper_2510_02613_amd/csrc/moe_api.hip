@@ -155,7 +155,36 @@ struct moe_layer {
     std::vector<hipEvent_t> load_ev;
     int n_pending = 0;
     hipEvent_t serve_ev = nullptr;  // "work enqueued on the serving stream so far", recorded per fill
+    moe_vpool *vpool[2] = {nullptr, nullptr};  // the page pools under w13 and w2 when the layer was told (moe_layer_bind_vpools)
 };
+
+namespace emoe {
+void layer_drop_vpool(moe_layer *l, const moe_vpool *p)
+{
+    for (int i = 0; i < 2; ++i)
+        if (l->vpool[i] == p) l->vpool[i] = nullptr;
+}
+}  // namespace emoe
+
+// With page pools bound: slot s must have a page under it in both.
+static moe_status_t check_backed(const moe_layer *l, int32_t s, const char *what)
+{
+    static const char *const name[2] = {"w13", "w2"};
+    for (int i = 0; i < 2; ++i)
+        if (l->vpool[i] && !vpool_backed(l->vpool[i], s))
+            return fail(MOE_ERR_MAP, "%s: slot %d has no page under it in the %s pool", what, s, name[i]);
+    return MOE_OK;
+}
+static moe_status_t check_owned_backed(const moe_layer *l, const std::vector<int32_t> &owner, const char *what)
+{
+    if (!l->vpool[0] && !l->vpool[1]) return MOE_OK;
+    for (int32_t s = 0; s < (int32_t)owner.size(); ++s)
+        if (owner[s] >= 0) {
+            const moe_status_t st = check_backed(l, s, what);
+            if (st != MOE_OK) return st;
+        }
+    return MOE_OK;
+}
 
 extern "C" {
 
@@ -219,6 +248,8 @@ void moe_layer_destroy(moe_layer_t *layer)
     if (layer->prof_on) moe_profile_enable(layer, 0);
     for (hipEvent_t ev : layer->load_ev) (void)hipEventDestroy(ev);
     if (layer->serve_ev) (void)hipEventDestroy(layer->serve_ev);
+    for (int i = 0; i < 2; ++i)
+        if (layer->vpool[i]) vpool_unbind(layer->vpool[i], layer);
     delete layer;
 }
 
@@ -280,6 +311,8 @@ namespace {
 moe_status_t install_table(moe_layer_t *l, std::vector<int32_t> &table, std::vector<int32_t> &owner, void *hip_stream)
 {
     int32_t *dst = (int32_t *)((char *)l->buf.workspace + l->lay.map);
+    const moe_status_t backed = check_owned_backed(l, owner, "the placement names a slot that cannot be read");
+    if (backed != MOE_OK) return backed;
     hipError_t e = hipSuccess;
     // slot fills enqueued by moe_load_expert: everything after this switch on hip_stream sees them complete
     for (int i = 0; i < l->n_pending && e == hipSuccess; ++i) e = hipStreamWaitEvent((hipStream_t)hip_stream, l->load_ev[i], 0);
@@ -388,6 +421,37 @@ moe_status_t moe_set_expert_replicas(moe_layer_t *l, const int32_t *host_rep_off
     return install_table(l, table, owner, hip_stream);
 }
 
+moe_status_t moe_layer_bind_vpools(moe_layer_t *l, moe_vpool_t *w13_pool, moe_vpool_t *w2_pool)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    const moe_config_t &c = l->cfg;
+    const size_t es = esize(c.act_dtype);
+    const size_t want[2] = {2 * (size_t)c.inter * c.hidden * es, (size_t)c.hidden * c.inter * es};
+    moe_vpool_t *pool[2] = {w13_pool, w2_pool};
+    const void *base[2] = {l->buf.w13, l->buf.w2};
+    static const char *const name[2] = {"w13", "w2"};
+    for (int i = 0; i < 2; ++i) {
+        if (!pool[i]) continue;
+        if (moe_vpool_base(pool[i]) != base[i]) return fail(MOE_ERR_ARG, "the %s pool does not start where the layer's %s does", name[i], name[i]);
+        if (moe_vpool_slot_bytes(pool[i]) != want[i])
+            return fail(MOE_ERR_ARG, "the %s pool has slots of %zu bytes, the layer's are %zu", name[i], moe_vpool_slot_bytes(pool[i]), want[i]);
+        if (moe_vpool_slots(pool[i]) < c.n_slots)
+            return fail(MOE_ERR_ARG, "the %s pool has %d slots, the layer has %d", name[i], moe_vpool_slots(pool[i]), c.n_slots);
+    }
+    moe_vpool *old[2] = {l->vpool[0], l->vpool[1]};
+    l->vpool[0] = w13_pool;
+    l->vpool[1] = w2_pool;
+    if (l->has_map) {   // the placement in force must already be readable
+        const moe_status_t st = check_owned_backed(l, l->slot_owner, "the active placement names a slot that cannot be read");
+        if (st != MOE_OK) { l->vpool[0] = old[0]; l->vpool[1] = old[1]; return st; }
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (old[i] && old[i] != l->vpool[i]) vpool_unbind(old[i], l);
+        if (l->vpool[i]) vpool_bind(l->vpool[i], l);
+    }
+    return MOE_OK;
+}
+
 moe_status_t moe_load_expert(moe_layer_t *l, int32_t slot, const void *src_w13, const void *src_w2,
                              void *copy_stream, void *serve_stream, int32_t copy_blocks)
 {
@@ -403,6 +467,8 @@ moe_status_t moe_load_expert(moe_layer_t *l, int32_t slot, const void *src_w13, 
         return fail(MOE_ERR_MAP, "slot %d holds %s %d of the active map: it cannot be refilled while forwards may read it", slot,
                     e >= c.n_experts ? "shared expert" : "expert", e >= c.n_experts ? e - c.n_experts : e);
     }
+    const moe_status_t backed = check_backed(l, slot, "the fill would write memory that is not there");
+    if (backed != MOE_OK) return backed;
     hipError_t e = hipSuccess;
     if (!l->serve_ev) e = hipEventCreateWithFlags(&l->serve_ev, hipEventDisableTiming);
     if (e == hipSuccess && (int)l->load_ev.size() == l->n_pending) {
@@ -458,6 +524,10 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
         return fail(MOE_ERR_ARG, "shared range [%d,%d) is not inside [0,%d]", shared_begin, shared_end, T);
     if (flags & ~(MOE_FLAG_IDENTITY_EXPERTS | MOE_FLAG_FORCE_GENERIC | MOE_FLAG_GATE_TILED | MOE_FLAG_PERMUTE_UNFUSED)) return fail(MOE_ERR_ARG, "unknown flag bits 0x%x", flags);
     if (!l->has_map) return fail(MOE_ERR_MAP, "no expert map installed: call moe_set_expert_map first");
+    {   // page pools bound: a page taken from under a slot of the placement in force would fault the pass
+        const moe_status_t backed = check_owned_backed(l, l->slot_owner, "the active placement names a slot whose page is gone");
+        if (backed != MOE_OK) return backed;
+    }
     if (T == 0) return MOE_OK;
     if (!x || !out) return fail(MOE_ERR_ARG, "x and out must be non-NULL");
     if (!aligned(x, 16) || !aligned(out, 16)) return fail(MOE_ERR_ARG, "x and out must be 16-byte aligned");

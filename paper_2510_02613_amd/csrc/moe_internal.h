@@ -125,6 +125,13 @@ int decode_tile_rows();
 hipError_t launch_identity_experts(const Pass &p, hipStream_t st);
 hipError_t launch_combine(const Pass &p, hipStream_t st);
 
+// A layer that was told which page pools its weights live in (moe_layer_bind_vpools) checks on the host that
+// every slot a placement names has a page under it; the pool tells the layer when it goes away.
+bool vpool_backed(const moe_vpool *pool, int32_t slot);          // moe_vpool.hip
+void vpool_bind(moe_vpool *pool, moe_layer *layer);
+void vpool_unbind(moe_vpool *pool, moe_layer *layer);
+void layer_drop_vpool(moe_layer *layer, const moe_vpool *pool);  // moe_api.hip
+
 constexpr int kGenericTileRows = 32;  // M-tile of the plain expert kernels
 
 // ---- small device helpers ---------------------------------------------------

@@ -16,6 +16,7 @@
 
 namespace emoe {
 moe_status_t set_error(moe_status_t st, const char *fmt, va_list ap);   // moe_api.hip
+void layer_drop_vpool(moe_layer *layer, const moe_vpool *pool);         // moe_api.hip
 }
 
 namespace {
@@ -45,7 +46,22 @@ struct moe_vpool {
     std::vector<int32_t> page_of;   // per virtual slot: page id or -1
     std::vector<Page> pages;
     hipMemAllocationProp prop = {};
+    std::vector<moe_layer *> bound;  // layers that check their placements against this pool
 };
+
+namespace emoe {
+bool vpool_backed(const moe_vpool *p, int32_t slot) { return slot >= 0 && slot < p->n_vslots && p->page_of[slot] >= 0; }
+void vpool_bind(moe_vpool *p, moe_layer *l)
+{
+    for (moe_layer *b : p->bound) if (b == l) return;
+    p->bound.push_back(l);
+}
+void vpool_unbind(moe_vpool *p, moe_layer *l)
+{
+    for (size_t i = 0; i < p->bound.size(); ++i)
+        if (p->bound[i] == l) { p->bound.erase(p->bound.begin() + i); return; }
+}
+}  // namespace emoe
 
 extern "C" {
 
@@ -152,9 +168,13 @@ moe_status_t moe_vpool_unmap(moe_vpool_t *p, int32_t vslot)
     return MOE_OK;
 }
 
+size_t moe_vpool_slot_bytes(const moe_vpool_t *p) { return p ? p->slot_bytes : 0; }
+int32_t moe_vpool_slots(const moe_vpool_t *p) { return p ? p->n_vslots : 0; }
+
 moe_status_t moe_vpool_destroy(moe_vpool_t *p)
 {
     if (!p) return MOE_OK;
+    for (moe_layer *l : p->bound) emoe::layer_drop_vpool(l, p);   // those layers stop checking against this pool
     hipError_t first = hipSuccess;
     for (int32_t s = 0; s < p->n_vslots; ++s)
         if (p->page_of[s] >= 0) {

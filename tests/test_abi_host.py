@@ -215,6 +215,10 @@ def test_virtual_pool_argument_checks_and_no_gpu():
     assert ei.value.status == B.MOE_ERR_ARG
     assert B.moe_vpool_base(None) == 0 and B.moe_vpool_page_of(None, 0) == -1
     B.moe_vpool_destroy(None)
+    assert B.moe_vpool_slot_bytes(None) == 0 and B.moe_vpool_slots(None) == 0
+    with pytest.raises(B.MoEError) as ei:
+        B.moe_layer_bind_vpools(None, None, None)
+    assert ei.value.status == B.MOE_ERR_ARG
     import torch
     if not torch.cuda.is_available():
         with pytest.raises(B.MoEError) as ei:      # no device: nothing to reserve addresses on

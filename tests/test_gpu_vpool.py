@@ -125,3 +125,80 @@ def test_virtual_pool_bookkeeping_errors():
         pool.page_free(b)
     finally:
         pool.close()
+
+
+def test_bound_pools_refuse_slots_without_a_page():
+    """A layer that knows its page pools turns what would be a GPU fault into MOE_ERR_MAP on the host: a
+    placement naming a slot without a page, a fill into one, a forward after a page of the placement in
+    force was taken away -- and runs as before once the page is back."""
+    import torch
+    from gpu_util import Case
+    from paper_2510_02613_amd import binding as B
+    from paper_2510_02613_amd.layer import VirtualPool, MoELayer
+    wl = MoEWorkload(name="vpool_guard", tokens=300, **MID)
+    H, I, S = wl.hidden, wl.inter, wl.n_slots
+    p13 = VirtualPool(S, (2 * I, H), torch.int16)
+    p2 = VirtualPool(S, (H, I), torch.int16)
+    other = VirtualPool(S, (H, I), torch.int16)
+    try:
+        for s in range(8):
+            p13.map(s, p13.page_alloc())
+            p2.map(s, p2.page_alloc())
+        p13.map(9, p13.page_alloc())                        # slot 9: a page in the w13 pool only
+        map_a = np.full(wl.n_experts, -1, np.int32)
+        map_a[:8] = np.arange(8)
+        case = Case(wl, expert_map=map_a, pools=(p13, p2))
+        layer = case.layer
+        out_a = _check(case)
+
+        bad = map_a.copy()
+        bad[8] = 9
+        with pytest.raises(B.MoEError) as ei:
+            layer.set_expert_map(bad)
+        assert ei.value.status == B.MOE_ERR_MAP and "w2 pool" in str(ei.value)
+        bad[8] = 10
+        with pytest.raises(B.MoEError) as ei:
+            layer.set_expert_map(bad)
+        assert ei.value.status == B.MOE_ERR_MAP and "w13 pool" in str(ei.value)
+        with pytest.raises(B.MoEError) as ei:
+            layer.set_expert_replicas([[e, 10] if e == 0 else ([e] if e < 8 else []) for e in range(wl.n_experts)])
+        assert ei.value.status == B.MOE_ERR_MAP
+        np.testing.assert_array_equal(case.run(), out_a)    # the placement in force is untouched
+
+        src = (layer.upload(case.inp["w13_experts"][8]), layer.upload(case.inp["w2_experts"][8]))
+        with pytest.raises(B.MoEError) as ei:
+            layer.load_expert_async(9, src[0], src[1], torch.cuda.Stream())
+        assert ei.value.status == B.MOE_ERR_MAP
+
+        torch.cuda.synchronize()                            # nothing in flight: a page of the active placement goes
+        page = p13.page_of(5)
+        p13.unmap(5)
+        with pytest.raises(B.MoEError) as ei:
+            case.run()
+        assert ei.value.status == B.MOE_ERR_MAP and "slot 5" in str(ei.value)
+        p13.map(5, page)                                    # the page kept its contents
+        np.testing.assert_array_equal(case.run(), out_a)
+
+        # binding checks: a pool that is not the layer's, and a placement in force that is not readable
+        with pytest.raises(B.MoEError) as ei:
+            B.moe_layer_bind_vpools(layer.handle, p13.handle, other.handle)
+        assert ei.value.status == B.MOE_ERR_ARG
+        with pytest.raises(B.MoEError) as ei:
+            B.moe_layer_bind_vpools(layer.handle, p2.handle, None)     # wrong slot size and base
+        assert ei.value.status == B.MOE_ERR_ARG
+        B.moe_layer_bind_vpools(layer.handle, None, None)   # unbound: the host no longer looks
+        p2.unmap(7)
+        page7 = p2.page_of(7)
+        assert page7 == -1
+        with pytest.raises(B.MoEError) as ei:
+            B.moe_layer_bind_vpools(layer.handle, p13.handle, p2.handle)
+        assert ei.value.status == B.MOE_ERR_MAP and "slot 7" in str(ei.value)
+        torch.cuda.synchronize()
+        # a pool that goes away before the layer takes its checks with it
+        B.moe_layer_bind_vpools(layer.handle, p13.handle, None)
+    finally:
+        torch.cuda.synchronize()
+        p13.close()
+        p2.close()
+        other.close()
+    case.layer.close()
