@@ -550,15 +550,33 @@ def measure_ceilings(torch, B, layer, stream):
     for _ in range(reps):
         B.moe_ceiling_stream(w_ptr, w_bytes, sink.data_ptr(), s)
     ev[3].record(stream)
+    # the same pool read in the access shape of the large-tile kernels' weight loaders (bf16 pools with whole 128-byte steps)
+    S, rows, H = layer.w13.shape
+    row_bytes = H * layer.w13.element_size()
+    tiles = S * (rows // 256)
+    shaped = layer.act_dtype == "bf16" and row_bytes % 128 == 0 and tiles > 0 and rows % 256 == 0
+    if shaped:
+        for nt in (False, True):
+            B.moe_ceiling_tile_stream(w_ptr, tiles, row_bytes, nt, s)    # warm
+        for i, nt in enumerate((False, True)):
+            for _ in range(reps):
+                B.moe_ceiling_tile_stream(w_ptr, tiles, row_bytes, nt, s)
+            ev[4 + i].record(stream)
     torch.cuda.synchronize()
     t_c = ev[0].elapsed_time(ev[1]) * 1e-3
     t_r = ev[1].elapsed_time(ev[2]) * 1e-3
     t_s = ev[2].elapsed_time(ev[3]) * 1e-3
-    return {"mfma_bf16_tflops_constant_operands": flops / t_c / 1e12,
-            "mfma_bf16_tflops_random_operands": flops / t_r / 1e12,
-            "stream_read_gbs": reps * w_bytes / t_s / 1e9, "stream_bytes": w_bytes, "stream_reps": reps,
-            "note": "sustained rates of this chip: register-only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup) "
-                    "on constant and on changing pseudo-random operands, and a plain read of the W13 pool"}
+    out = {"mfma_bf16_tflops_constant_operands": flops / t_c / 1e12,
+           "mfma_bf16_tflops_random_operands": flops / t_r / 1e12,
+           "stream_read_gbs": reps * w_bytes / t_s / 1e9, "stream_bytes": w_bytes, "stream_reps": reps,
+           "note": "sustained rates of this chip: register-only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup) "
+                   "on constant and on changing pseudo-random operands, a plain read of the W13 pool, and the same pool "
+                   "read as the large-tile kernels' weight loaders read it (256-row tiles, 128 bytes per row per step, "
+                   "global -> LDS, default and non-temporal)"}
+    if shaped:
+        out["tile_stream_read_gbs"] = reps * w_bytes / (ev[3].elapsed_time(ev[4]) * 1e-3) / 1e9
+        out["tile_stream_read_nt_gbs"] = reps * w_bytes / (ev[4].elapsed_time(ev[5]) * 1e-3) / 1e9
+    return out
 
 
 def cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, target_s):

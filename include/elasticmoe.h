@@ -315,10 +315,20 @@ moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
  *                       power), 0 small constants (the issue-rate ceiling).
  *   moe_ceiling_stream: reads `bytes` (rounded down to 16) of device memory at `buf`
  *                       (16-byte aligned) once, 16 bytes per lane.
+ *   moe_ceiling_tile_stream: the weight stream of the large-tile expert kernels with nothing
+ *                       else running: reads n_tiles x 256 x row_bytes bytes at `buf` (device,
+ *                       16-byte aligned; the caller owns at least that much) as n_tiles tiles of
+ *                       256 consecutive rows, one workgroup per tile, 128 bytes of every row per
+ *                       step, global -> LDS, 2 steps in flight.  row_bytes: a multiple of 128
+ *                       below 2^24 (the row stride of a weight matrix: hidden or inter elements).
+ *                       non_temporal != 0 marks the copies read-once, as the kernels do for a
+ *                       slot whose rows are one tile.  MOE_ERR_ARG on anything else; nothing
+ *                       is written.
  */
 moe_status_t moe_ceiling_mfma(int32_t blocks, int32_t iters, int32_t random_operands, float *sink,
                               void *hip_stream, double *flops);
 moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void *hip_stream);
+moe_status_t moe_ceiling_tile_stream(const void *buf, int32_t n_tiles, size_t row_bytes, int32_t non_temporal, void *hip_stream);
 
 /*
  * A weight pool as ONE contiguous virtual tensor over separately allocated physical pages

@@ -26,7 +26,7 @@ EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
            "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
            "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_vpool_slot_bytes",
-           "moe_vpool_slots", "moe_layer_bind_vpools", "moe_forward_static",
+           "moe_vpool_slots", "moe_layer_bind_vpools", "moe_ceiling_tile_stream", "moe_forward_static",
            "moe_pool_export", "moe_pool_open", "moe_pool_close")
 MOE_IPC_HANDLE_BYTES = 64
 MOE_STATIC_SCRATCH_BYTES = 32 << 20
@@ -137,6 +137,8 @@ def lib() -> ctypes.CDLL:
                                        ctypes.POINTER(ctypes.c_double)]
         L.moe_ceiling_stream.restype = ctypes.c_int
         L.moe_ceiling_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_ceiling_tile_stream.restype = ctypes.c_int
+        L.moe_ceiling_tile_stream.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p]
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_last_error.argtypes = []
         _lib = L
@@ -312,6 +314,12 @@ def moe_ceiling_mfma(blocks: int, iters: int, random_operands: bool, sink_ptr: i
 def moe_ceiling_stream(buf_ptr: int, nbytes: int, sink_ptr: int, stream: int = 0) -> None:
     """Enqueue one streaming read of nbytes of device memory."""
     _check(lib().moe_ceiling_stream(ctypes.c_void_p(buf_ptr), ctypes.c_size_t(nbytes), ctypes.c_void_p(sink_ptr), ctypes.c_void_p(stream)))
+
+
+def moe_ceiling_tile_stream(buf_ptr: int, n_tiles: int, row_bytes: int, non_temporal: bool, stream: int = 0) -> None:
+    """Enqueue one read of n_tiles tiles of 256 rows x row_bytes in the access shape of the large-tile kernels' weight loaders."""
+    _check(lib().moe_ceiling_tile_stream(ctypes.c_void_p(buf_ptr), ctypes.c_int32(n_tiles), ctypes.c_size_t(row_bytes),
+                                         ctypes.c_int32(int(non_temporal)), ctypes.c_void_p(stream)))
 
 
 def moe_layer_destroy(layer) -> None:

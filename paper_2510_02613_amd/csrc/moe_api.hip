@@ -242,6 +242,17 @@ moe_status_t moe_ceiling_stream(const void *buf, size_t bytes, float *sink, void
     return MOE_OK;
 }
 
+moe_status_t moe_ceiling_tile_stream(const void *buf, int32_t n_tiles, size_t row_bytes, int32_t non_temporal, void *hip_stream)
+{
+    if (!buf || !aligned(buf, 16)) return fail(MOE_ERR_ARG, "buf must be non-NULL and 16-byte aligned");
+    if (n_tiles <= 0) return fail(MOE_ERR_ARG, "n_tiles %d is not positive", n_tiles);
+    if (row_bytes < 128 || row_bytes % 128 != 0 || row_bytes * 256 >= ((size_t)1 << 32))
+        return fail(MOE_ERR_ARG, "row_bytes %zu must be a multiple of 128 below 2^24", row_bytes);
+    const hipError_t e = launch_ceiling_tile_stream(buf, n_tiles, row_bytes, non_temporal, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(MOE_ERR_HIP, "ceiling launch failed: %s", hipGetErrorString(e));
+    return MOE_OK;
+}
+
 void moe_layer_destroy(moe_layer_t *layer)
 {
     if (!layer) return;

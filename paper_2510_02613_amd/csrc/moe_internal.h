@@ -119,6 +119,7 @@ size_t mfma8_partial_bytes();   // workspace for the partial sums of tiles whose
 hipError_t launch_ceiling_mfma(int blocks, int iters, int random_operands, float *sink, hipStream_t st);
 double ceiling_mfma_flops(int blocks, int iters);
 hipError_t launch_ceiling_stream(const void *buf, size_t bytes, float *sink, hipStream_t st);
+hipError_t launch_ceiling_tile_stream(const void *buf, int n_tiles, size_t row_bytes, int non_temporal, hipStream_t st);
 // weight-streaming variant for decode-sized batches (M-tiles of 16 rows)
 hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st);
 int decode_tile_rows();

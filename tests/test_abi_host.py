@@ -226,6 +226,18 @@ def test_virtual_pool_argument_checks_and_no_gpu():
         assert ei.value.status in (B.MOE_ERR_HIP, B.MOE_ERR_UNSUPPORTED)
 
 
+def test_ceiling_argument_checks():
+    """The measuring-stick calls reject bad arguments before anything is launched."""
+    L = B.lib()
+    import ctypes
+    assert L.moe_ceiling_stream(None, ctypes.c_size_t(4096), None, None) == B.MOE_ERR_ARG
+    buf = ctypes.c_void_p(1 << 20)
+    for n_tiles, row_bytes in ((0, 4096), (4, 0), (4, 100), (4, 1 << 24)):
+        assert L.moe_ceiling_tile_stream(buf, n_tiles, ctypes.c_size_t(row_bytes), 0, None) == B.MOE_ERR_ARG
+    assert L.moe_ceiling_tile_stream(None, 4, ctypes.c_size_t(4096), 0, None) == B.MOE_ERR_ARG
+    assert L.moe_ceiling_tile_stream(ctypes.c_void_p((1 << 20) + 8), 4, ctypes.c_size_t(4096), 0, None) == B.MOE_ERR_ARG
+
+
 def test_pool_export_argument_checks():
     import ctypes
     L = B.lib()
