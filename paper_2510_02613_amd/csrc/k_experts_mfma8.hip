@@ -62,11 +62,20 @@ constexpr int kRows = kBN + kBM;           // LDS rows per stage
 constexpr int kBKW = 64;                   // weight K-step: 128 bytes per row = one whole cache line
 constexpr int kWStage = kBN * kBKW * 2;    // 32 KB of weight rows per weight step
 constexpr int kXStage = kBM * kBK * 2;     // 40 KB of token rows per K-step
+#ifdef EMOE_TIMING_W3
+constexpr int kNW = 3;                     // TIMING ONLY: a third weight stage, two steps in flight (see kXBase)
+#else
 constexpr int kNW = 2;                     // weight ring depth: one step multiplied, one in flight
+#endif
 constexpr int kNX = 2;                     // token ring depth
 constexpr int kWPieces = kWStage / 1024 / 4;   // 8: 1 KB pieces (8 rows x 128 B) per weight-loader wavefront per weight step
 constexpr int kXPieces = kXStage / 1024 / 4;   // 10: 1 KB pieces (8 rows x 128 B) per token-loader wavefront per K-step
-constexpr int kRingBytes = kNW * kWStage + kNX * kXStage;
+#ifdef EMOE_TIMING_W3
+constexpr int kXBase = kNW * kWStage - 16384;   // the token stages overlap the third weight stage (it does not fit beside them): garbage results
+#else
+constexpr int kXBase = kNW * kWStage;      // the token ring follows the weight ring
+#endif
+constexpr int kRingBytes = kXBase + kNX * kXStage;
 constexpr int kXcds = 8;
 constexpr int kMaxPartialSets = 256;        // partial-sum sets the workspace has room for: one round of a 256-unit chip
 constexpr int kTC = kMaxTT / 2;            // token tiles per wavefront
@@ -85,6 +94,7 @@ struct WaveCtx {
     uint32_t off[kXPieces > kWPieces ? kXPieces : kWPieces];               // this lane's byte offset (from the matrix base) of each piece it stages, k = 0
     uint32_t woff[kBKW / 16], xoff[kBK / 16]; // LDS byte offsets (inside a stage) of this lane's operand rows per sub-step
     int wave, lane, wm, wn, n_tt;
+    uint32_t wkb;                         // EMOE_TIMING_KMAJOR: elements between the k-blocks of a slot
     bool stream_w;                        // this tile's weight rows are read by no other tile: copy them non-temporally
     int xlive;                            // token-loader wavefronts: how many of their pieces hold rows that exist
 };
@@ -126,7 +136,8 @@ __device__ __forceinline__ void dma_piece(const void *base, uint32_t byte_off, u
 __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr, int k0)
 {
     // Timing-only builds (results are garbage): leave out the weight copies, the token copies or (below) the
-    // multiply, to time what is left.  Off unless the build defines the macro.
+    // multiply, to time what is left; EMOE_TIMING_W3 and EMOE_TIMING_KMAJOR time a third weight stage and a
+    // k-block-major pool without building either.  Off unless the build defines the macro.
 #ifdef EMOE_TIMING_NO_W
     if (c.wave < 4) return;
 #endif
@@ -134,7 +145,11 @@ __device__ __forceinline__ void issue_step(const WaveCtx &c, uint32_t slot_addr,
     if (c.wave >= 4) return;
 #endif
     if (c.wave < 4) {
+#ifdef EMOE_TIMING_KMAJOR
+        const uint16_t *b = c.wbase + (size_t)(k0 / kBKW) * c.wkb;   // TIMING ONLY: the pool read as if it were [K/64][rows][64]
+#else
         const uint16_t *b = c.wbase + k0;
+#endif
         if (c.stream_w) {
 #pragma unroll
             for (int i = 0; i < kWPieces; ++i) dma_piece<true>(b, c.off[i], slot_addr + (c.wave * kWPieces + i) * 1024);
@@ -223,17 +238,33 @@ __device__ __forceinline__ void k_loop(const WaveCtx &c, const char *ring, int K
     // through the multiply: a compute unit returns copies in issue order, and token copies (L2 hits)
     // issued just behind a burst of weight copies would wait out that burst's HBM latency.
     const bool wloader = c.wave < 4;
-    const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
+    const uint32_t wring = lds_addr(ring), xring = wring + kXBase;
     int slot = 0;
+#ifdef EMOE_TIMING_W3
+    // TIMING ONLY: weight step kt+2 goes out half way through step kt (the caller issued steps 0 and 1)
+    int ws = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 1 < KT;
+        if (wloader && more) wait_loads<kWPieces>(); else wait_loads<0>();   // step kt has landed; kt+1 may be in flight
+        __syncthreads();
+        if (!wloader && more) issue_step(c, xring + (slot ^ 1) * kXStage, (kt + 1) * kBK);
+        const int w2 = ws == 0 ? 2 : ws - 1;    // stage of step kt+2 = stage of step kt-1
+        multiply_stage<NTC>(c, ring + ws * kWStage, ring + kXBase + slot * kXStage, acc,
+                            [&]() { if (wloader && kt + 2 < KT) issue_step(c, wring + w2 * kWStage, (kt + 2) * kBKW); });
+        slot ^= 1;
+        ws = ws == 2 ? 0 : ws + 1;
+    }
+#else
     for (int kt = 0; kt < KT; ++kt) {
         wait_loads<0>();   // this wavefront's share of step kt has landed (nothing younger is in flight)
         __syncthreads();   // everyone's share of step kt is in LDS; everyone is done reading step kt-1
         const bool more = kt + 1 < KT;
         if (!wloader && more) issue_step(c, xring + (slot ^ 1) * kXStage, (kt + 1) * kBK);
-        multiply_stage<NTC>(c, ring + slot * kWStage, ring + kNW * kWStage + slot * kXStage, acc,
+        multiply_stage<NTC>(c, ring + slot * kWStage, ring + kXBase + slot * kXStage, acc,
                             [&]() { if (wloader && more) issue_step(c, wring + (slot ^ 1) * kWStage, (kt + 1) * kBKW); });
         slot ^= 1;
     }
+#endif
 }
 
 // Partial sums of a tile whose contraction is shared out over several workgroups (the tail of a
@@ -409,7 +440,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     const int w1 = kPhase == 1 ? (int)((long long)(part + 1) * wsteps / n_parts) : wsteps;
     const uint16_t *W = (const uint16_t *)(kFirst ? p.w13 : p.w2) + (size_t)mt.slot * (kFirst ? 2 : 1) * (size_t)p.I * p.H;
     const uint16_t *A = (const uint16_t *)(kFirst ? p.x : p.h);
+#ifdef EMOE_TIMING_KMAJOR
+    c.wkb = (uint32_t)(kFirst ? 2 * p.I : p.H) * kBKW;
+    c.wbase = W + (size_t)w0 * c.wkb;
+#else
     c.wbase = W + w0 * kBKW;      // rows are K-contiguous: the piece offsets below are relative to the range's first k
+#endif
     c.abase = A + w0 * kBKW;
     if (c.wave < 4) {
 #pragma unroll
@@ -426,7 +462,13 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
             } else {
                 g = min(n0 + row, N - 1);
             }
+#ifdef EMOE_TIMING_KMAJOR
+            // the workgroup's 256 weight rows as one contiguous 32 KB block per k-block (stays inside the slot)
+            (void)g; (void)chunk;
+            c.off[i] = ((uint32_t)min((n0 / BNO) * kBN + row, (kFirst ? 2 * p.I : p.H) - 1) * kBKW + (c.lane & 7) * 8) * 2;
+#else
             c.off[i] = ((uint32_t)g * K + chunk * 8) * 2;
+#endif
         }
     } else {
 #pragma unroll
@@ -451,8 +493,11 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
 
     const int KT = w1 - w0;
     if (kPhase != 2) {
-        const uint32_t wring = lds_addr(ring), xring = wring + kNW * kWStage;
+        const uint32_t wring = lds_addr(ring), xring = wring + kXBase;
         if (KT > 0) issue_step(c, c.wave < 4 ? wring : xring, 0);
+#ifdef EMOE_TIMING_W3
+        if (KT > 1 && c.wave < 4) issue_step(c, wring + kWStage, kBKW);
+#endif
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
