@@ -133,10 +133,10 @@ class MoELayer:
                                 self.w13.data_ptr(), self.w2.data_ptr(),
                                 self.workspace.data_ptr(), ws_bytes)
         self.handle = B.moe_layer_create(self.cfg, self.buf)
-        if w13_pool is not None or w2_pool is not None:
-            # the host then refuses placements, fills and forwards that would touch a slot without a page
-            B.moe_layer_bind_vpools(self.handle, None if w13_pool is None else w13_pool.handle,
-                                    None if w2_pool is None else w2_pool.handle)
+        vp = [p.handle if isinstance(p, VirtualPool) else None for p in (w13_pool, w2_pool)]
+        if vp[0] is not None or vp[1] is not None:
+            # page pools: the host then refuses placements, fills and forwards that would touch a slot without a page
+            B.moe_layer_bind_vpools(self.handle, vp[0], vp[1])
 
     def close(self):
         if getattr(self, "handle", None) is not None:
