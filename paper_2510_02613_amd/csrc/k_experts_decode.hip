@@ -7,17 +7,17 @@
 // tile list, built from the active expert map (Sec. 3.2 / 4.6: placement is data,
 // not layout), only names slots that have rows.
 //
-// One wavefront owns a block of weight rows of one M-tile (<= 16 grouped rows) and
-// walks the whole contraction: GEMM-1 takes 16 gate rows and the 16 matching up rows
-// (so silu(g)*u is formed in registers), GEMM-2 takes 16 consecutive W2 rows.  Weights
-// and token rows go straight from global memory into MFMA operand layout, as in
-// the gate kernel: for a K-chunk of 128, lane (n = l%16, q = l/16) reads the 32 k
-// {jj*32 + q*8 + i} of row n with four 16-byte loads issued back to back, so every
-// row contributes a contiguous 256-byte run per chunk.  v_mfma_f32_16x16x32_bf16
-// with the weights as first operand gives lane (j = l%16, q) the outputs of token
-// j for weight rows 4q..4q+3: one 8-byte store.  The next chunk's loads are in
-// flight during the current chunk's MFMAs; with 4 wavefronts per SIMD that keeps
-// more than 128 KB per compute unit on its way from HBM.
+// A task is a block of weight rows of one M-tile (<= 16 grouped rows): GEMM-1 takes 16
+// gate rows and the 16 matching up rows (so silu(g)*u is formed in registers), GEMM-2
+// 32 consecutive W2 rows.  A task is one workgroup of four wavefronts, each walking a
+// quarter of the contraction.  Weights and token rows go straight from global memory
+// into MFMA operand layout, as in the gate kernel: for a K-chunk of 128, lane
+// (n = l%16, q = l/16) reads the 32 k {jj*32 + q*8 + i} of row n with four 16-byte
+// loads issued back to back, so every row contributes a contiguous 256-byte run per
+// chunk.  v_mfma_f32_16x16x32_bf16 with the weights as first operand gives lane
+// (j = l%16, q) the outputs of token j for weight rows 4q..4q+3: one 8-byte store.
+// The next chunk's loads are in flight during the current chunk's MFMAs; with 4
+// wavefronts per SIMD that keeps more than 128 KB per compute unit on its way from HBM.
 #include "moe_internal.h"
 
 namespace emoe {
@@ -26,8 +26,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 64;    // one wavefront per workgroup: tasks are dealt to compute units one by one, which
-                                // balances a grid that is only about one round of the chip deep
+constexpr int kThreads = 64;    // a wavefront; a workgroup is one task: the kSplit wavefronts that share its contraction
 constexpr int kTileRows = 16;   // grouped rows per M-tile (one MFMA N dimension)
 constexpr int kWRows = 32;      // weight rows per wavefront
 
@@ -42,18 +41,27 @@ __device__ __forceinline__ void load_run(Run &r, const uint16_t *row, int k0, in
     }
 }
 
-constexpr int kBlocks2 = 1;   // 16-row weight blocks per wavefront in GEMM-2: its contraction is short (I), and
-                              // twice as many, half as long tasks keep more of the chip streaming to the end
+constexpr int kBlocks2 = 2;   // 16-row weight blocks per task in GEMM-2
+// Wavefronts that share a task's contraction: each takes a contiguous quarter of the K-chunks, the first adds
+// the four sums in K order (through LDS) and stores.  A wavefront's stream is latency bound (one chunk in
+// flight), so a launch ends with a tail as long as one task in which ever fewer wavefronts stream; with four
+// wavefronts per task that tail is a quarter as long, and the tasks of a launch (several rounds of the chip's
+// wavefront slots in GEMM-2) are dealt to the compute units in finer pieces.  Measured on the DeepSeek-V3-shaped
+// rank with 64 tokens: GEMM-1 291 -> 277 us, GEMM-2 161 -> 140 us (2 or 8 wavefronts per task: slower).
+constexpr int kSplit1 = 4;
+constexpr int kSplit2 = 4;
 
 template <bool kFirst>
-__global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
+__global__ __launch_bounds__(kFirst ? kThreads * kSplit1 : kThreads * kSplit2) void k_expert_decode(Pass p)
 {
+    constexpr int NS = kFirst ? kSplit1 : kSplit2;                // wavefronts of this workgroup (one task)
     const int K = kFirst ? p.H : p.I;
     const int N = kFirst ? p.I : p.H;                       // output columns
     constexpr bool kTwo = kFirst || kBlocks2 == 2;          // two weight rows per lane
     constexpr int COLS = kFirst ? kWRows / 2 : 16 * kBlocks2;   // output columns per wavefront
     const int groups = (N + COLS - 1) / COLS;               // wavefront tasks per M-tile
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int ks = NS > 1 ? (int)(threadIdx.x >> 6) : 0;    // which part of the contraction
     const int task = blockIdx.x;
     const int tile = task / groups;
     if (tile >= *p.n_tiles) return;
@@ -70,16 +78,19 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
     const int tr = mt.row_begin + min(n, mt.rows - 1);
     const uint16_t *xr = (const uint16_t *)(kFirst ? p.x : p.h) + (size_t)(kFirst ? p.perm[tr] : tr) * K;
 
+    // this wavefront's K-chunks: [kbeg, kend)
+    const int chunks = (K + 127) >> 7, per = (chunks + NS - 1) / NS;
+    const int kbeg = min(ks * per, chunks) * 128, kend = min(min((ks + 1) * per, chunks) * 128, K), kstep = 128;
     f32x4 acc_a = {0.f, 0.f, 0.f, 0.f}, acc_b = {0.f, 0.f, 0.f, 0.f};
     Run ca, cb, cx, na, nb, nx;
-    load_run(ca, wa, 0, q, K);
-    if (kTwo) load_run(cb, wb, 0, q, K);
-    load_run(cx, xr, 0, q, K);
-    for (int k0 = 0; k0 < K; k0 += 128) {
-        if (k0 + 128 < K) {
-            load_run(na, wa, k0 + 128, q, K);
-            if (kTwo) load_run(nb, wb, k0 + 128, q, K);
-            load_run(nx, xr, k0 + 128, q, K);
+    load_run(ca, wa, kbeg, q, K);
+    if (kTwo) load_run(cb, wb, kbeg, q, K);
+    load_run(cx, xr, kbeg, q, K);
+    for (int k0 = kbeg; k0 < kend; k0 += kstep) {
+        if (k0 + kstep < kend) {
+            load_run(na, wa, k0 + kstep, q, K);
+            if (kTwo) load_run(nb, wb, k0 + kstep, q, K);
+            load_run(nx, xr, k0 + kstep, q, K);
         }
         __builtin_amdgcn_sched_barrier(0);  // the prefetch must be issued before this chunk's MFMAs, not after
 #pragma unroll
@@ -90,6 +101,18 @@ __global__ __launch_bounds__(kThreads) void k_expert_decode(Pass p)
         ca = na; cb = nb; cx = nx;
     }
 
+    if constexpr (NS > 1) {   // the parts' sums, added in K order by the first wavefront
+        __shared__ f32x4 part[NS - 1 > 0 ? NS - 1 : 1][kTwo ? 2 : 1][64];
+        if (ks > 0) { part[ks - 1][0][lane] = acc_a; if (kTwo) part[ks - 1][kTwo ? 1 : 0][lane] = acc_b; }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) {
+            const f32x4 a = part[s][0][lane];
+            acc_a[0] += a[0]; acc_a[1] += a[1]; acc_a[2] += a[2]; acc_a[3] += a[3];
+            if (kTwo) { const f32x4 b = part[s][kTwo ? 1 : 0][lane]; acc_b[0] += b[0]; acc_b[1] += b[1]; acc_b[2] += b[2]; acc_b[3] += b[3]; }
+        }
+    }
     // lane holds token n, weight rows 4q..4q+3 of each of its two row blocks
     if (n >= mt.rows) return;
     uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y) + (size_t)(mt.row_begin + n) * N;
@@ -121,11 +144,11 @@ hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st)
     if (which == 0) {
         const int groups = (p.I + kWRows / 2 - 1) / (kWRows / 2);
         const int blocks = p.max_tiles * groups;
-        hipLaunchKernelGGL((k_expert_decode<true>), dim3(blocks), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_expert_decode<true>), dim3(blocks), dim3(kThreads * kSplit1), 0, st, p);
     } else {
         const int groups = (p.H + 16 * kBlocks2 - 1) / (16 * kBlocks2);
         const int blocks = p.max_tiles * groups;
-        hipLaunchKernelGGL((k_expert_decode<false>), dim3(blocks), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_expert_decode<false>), dim3(blocks), dim3(kThreads * kSplit2), 0, st, p);
     }
     return hipGetLastError();
 }
