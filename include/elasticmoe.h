@@ -294,11 +294,14 @@ moe_status_t moe_workspace_view(const moe_layer_t *layer, moe_workspace_view_t *
  * kept.  moe_profile_read waits for the recorded forward `back` recordings ago
  * (0 = most recent) and writes the milliseconds of each phase to ms[MOE_N_PHASES].
  * Enabling creates the events (host objects), disabling or destroying the layer
- * destroys them.
+ * destroys them.  moe_profile_select(phase) restricts the recording to the two events
+ * around ONE phase (moe_profile_read then writes 0 for the others), -1 (the default)
+ * records all six; it forgets what was recorded before.
  */
 enum { MOE_PHASE_GATE = 0, MOE_PHASE_PERMUTE = 1, MOE_PHASE_GEMM1 = 2, MOE_PHASE_GEMM2 = 3,
        MOE_PHASE_COMBINE = 4, MOE_N_PHASES = 5 };
 moe_status_t moe_profile_enable(moe_layer_t *layer, int32_t enable);
+moe_status_t moe_profile_select(moe_layer_t *layer, int32_t phase);
 moe_status_t moe_profile_read(moe_layer_t *layer, int32_t back, float *ms);
 
 /*

@@ -26,7 +26,7 @@ EXPORTS = ("moe_workspace_bytes", "moe_layer_create", "moe_set_expert_map", "moe
            "moe_profile_read", "moe_ceiling_mfma", "moe_ceiling_stream", "moe_forward_routed",
            "moe_load_expert", "moe_set_expert_replicas", "moe_vpool_create", "moe_vpool_base", "moe_vpool_page_alloc", "moe_vpool_page_free",
            "moe_vpool_map", "moe_vpool_unmap", "moe_vpool_page_of", "moe_vpool_destroy", "moe_vpool_slot_bytes",
-           "moe_vpool_slots", "moe_layer_bind_vpools", "moe_ceiling_tile_stream", "moe_forward_static",
+           "moe_vpool_slots", "moe_layer_bind_vpools", "moe_ceiling_tile_stream", "moe_profile_select", "moe_forward_static",
            "moe_pool_export", "moe_pool_open", "moe_pool_close")
 MOE_IPC_HANDLE_BYTES = 64
 MOE_STATIC_SCRATCH_BYTES = 32 << 20
@@ -130,6 +130,8 @@ def lib() -> ctypes.CDLL:
         L.moe_layer_destroy.argtypes = [ctypes.c_void_p]
         L.moe_profile_enable.restype = ctypes.c_int
         L.moe_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        L.moe_profile_select.restype = ctypes.c_int
+        L.moe_profile_select.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.moe_profile_read.restype = ctypes.c_int
         L.moe_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)]
         L.moe_ceiling_mfma.restype = ctypes.c_int
@@ -295,6 +297,11 @@ def moe_workspace_view(layer) -> MoEWorkspaceView:
 def moe_profile_enable(layer, enable: int) -> None:
     """0 = off, n > 0 = record the phase events of every n-th forward."""
     _check(lib().moe_profile_enable(layer, int(enable)))
+
+
+def moe_profile_select(layer, phase: int) -> None:
+    """Record only the two events around one phase (-1: all phases again)."""
+    _check(lib().moe_profile_select(layer, int(phase)))
 
 
 def moe_profile_read(layer, back: int = 0):

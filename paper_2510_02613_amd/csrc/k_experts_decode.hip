@@ -51,9 +51,83 @@ constexpr int kBlocks2 = 2;   // 16-row weight blocks per task in GEMM-2
 constexpr int kSplit1 = 4;
 constexpr int kSplit2 = 4;
 
-template <bool kFirst>
+// Self-derived tiles (GEMM-1 of passes with at most 64 tokens and 64 slots whose selection kernel left per-block
+// slot masks): with so few tokens the offsets / permutation / tile-list kernel is pure latency in front of the
+// weight stream, and everything a GEMM-1 workgroup needs from it follows from 4 count bytes per slot.  So that
+// kernel is not launched: every wavefront adds up the counts itself (lane s = slot s), finds the slot and chunk
+// of its tile with a wavefront scan, and reads its rows' tokens off the slot's block masks; workgroup 0 of the
+// same launch writes the tables that GEMM-2, the combine and the workspace view read, while the others stream.
+constexpr int kSelfMaxSlots = 64, kSelfMaxBlocks = 4;
+
+// position of the r-th (0-based) set bit of m; m has more than r bits set
+__device__ __forceinline__ int nth_set_bit(unsigned long long m, int r)
+{
+    int pos = 0;
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1) {
+        const int cnt = __popcll(m & ((1ull << w) - 1ull));
+        if (r >= cnt) { r -= cnt; m >>= w; pos += w; }
+    }
+    return pos;
+}
+
+// the count bytes of slot s that exist (blocks past nb hold nothing defined)
+__device__ __forceinline__ uint32_t self_counts(const Pass &p, int s, int nb)
+{
+    const uint32_t w = *(const uint32_t *)(p.blk_cnt + (size_t)s * fused_row_stride(nb));
+    return nb >= 4 ? w : w & ((1u << (8 * nb)) - 1u);
+}
+
+// Workgroup 0: counts, offsets, tile list (slot order, chunks of kTileRows), permutation and its inverse --
+// the tables of the bookkeeping kernels, for the few-token case.  256 threads.
+__device__ void self_tables(const Pass &p)
+{
+    __shared__ int32_t s_cb[kSelfMaxSlots][kSelfMaxBlocks];   // rows of slot s in block b
+    __shared__ int32_t s_off[kSelfMaxSlots];
+    const int tid = threadIdx.x, S = p.S, nb = (p.T + kFusedTokens - 1) / kFusedTokens;
+    if (tid < S) {
+        const uint32_t w = self_counts(p, tid, nb);
+#pragma unroll
+        for (int b = 0; b < kSelfMaxBlocks; ++b) s_cb[tid][b] = (int)((w >> (8 * b)) & 0xffu);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int row = 0, tl = 0;
+        for (int s = 0; s < S; ++s) {
+            const int c = s_cb[s][0] + s_cb[s][1] + s_cb[s][2] + s_cb[s][3];
+            const int nt = (c + kTileRows - 1) / kTileRows;
+            p.counts[s] = c;
+            p.offs[s] = row;
+            s_off[s] = row;
+            for (int i = 0; i < nt; ++i, ++tl)
+                if (tl < p.max_tiles) {
+                    MTile mt;
+                    mt.slot = s; mt.row_begin = row + i * kTileRows; mt.rows = min(kTileRows, c - i * kTileRows); mt.single = nt == 1;
+                    p.tiles[tl] = mt;
+                }
+            row += c;
+        }
+        p.offs[S] = row;
+        *p.n_tiles = min(tl, p.max_tiles);
+    }
+    __syncthreads();
+    for (int a = tid; a < p.T * p.kk; a += blockDim.x) {
+        const int sr = p.slot_rank[a];
+        int row = -1;
+        if (sr >= 0) {
+            const int slot = sr >> 12, rank = sr & 0xfff, t = a / p.kk, b = t / kFusedTokens;
+            row = s_off[slot] + rank;
+            for (int b2 = 0; b2 < b; ++b2) row += s_cb[slot][b2];
+            p.perm[row] = t;
+        }
+        p.inv[a] = row;
+    }
+}
+
+template <bool kFirst, bool kSelf = false>
 __global__ __launch_bounds__(kFirst ? kThreads * kSplit1 : kThreads * kSplit2) void k_expert_decode(Pass p)
 {
+    static_assert(!kSelf || kFirst, "only GEMM-1 derives its tiles itself");
     constexpr int NS = kFirst ? kSplit1 : kSplit2;                // wavefronts of this workgroup (one task)
     const int K = kFirst ? p.H : p.I;
     const int N = kFirst ? p.I : p.H;                       // output columns
@@ -62,12 +136,45 @@ __global__ __launch_bounds__(kFirst ? kThreads * kSplit1 : kThreads * kSplit2) v
     const int groups = (N + COLS - 1) / COLS;               // wavefront tasks per M-tile
     const int lane = threadIdx.x & 63;
     const int ks = NS > 1 ? (int)(threadIdx.x >> 6) : 0;    // which part of the contraction
-    const int task = blockIdx.x;
+    int task = blockIdx.x;
+    if (kSelf) {
+        if (task == 0) { self_tables(p); return; }
+        task -= 1;
+    }
     const int tile = task / groups;
-    if (tile >= *p.n_tiles) return;
-    const MTile mt = p.tiles[tile];
-    const int n0 = (task % groups) * COLS;
     const int n = lane & 15, q = lane >> 4;
+    MTile mt;
+    int self_token = 0;                                     // kSelf: the token of this lane's row
+    if (kSelf) {
+        const int nb = (p.T + kFusedTokens - 1) / kFusedTokens, stride = fused_row_stride(nb);
+        // lane s: rows and tiles of slot s, then inclusive sums over the slots (rows in the high half)
+        int c = 0;
+        if (lane < p.S) c = (int)__builtin_amdgcn_sad_u8(self_counts(p, lane, nb), 0u, 0u);
+        const int nt = (c + kTileRows - 1) / kTileRows;
+        int incl = (c << 16) | nt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        const unsigned long long owners = __ballot((incl & 0xffff) > tile);
+        if (owners == 0) return;                            // past the last tile (the same in every wavefront)
+        const int s = __ffsll((long long)owners) - 1;
+        const int before = __shfl(incl - ((c << 16) | nt), s, 64), cs = __shfl(c, s, 64);
+        const int chunk = tile - (before & 0xffff);
+        mt.slot = s;
+        mt.row_begin = (before >> 16) + chunk * kTileRows;
+        mt.rows = min(kTileRows, cs - chunk * kTileRows);
+        mt.single = cs <= kTileRows;
+        // the slot's tokens, ascending: bit t of the block masks side by side
+        unsigned long long m = 0;
+        for (int b = 0; b < nb; ++b) m |= (unsigned long long)((uint32_t)p.blk_hist[(size_t)s * stride + b] & 0xffffu) << (16 * b);
+        self_token = nth_set_bit(m, chunk * kTileRows + min(n, mt.rows - 1));
+    } else {
+        if (tile >= *p.n_tiles) return;
+        mt = p.tiles[tile];
+    }
+    const int n0 = (task % groups) * COLS;
 
     const uint16_t *W = (const uint16_t *)(kFirst ? p.w13 : p.w2) + (size_t)mt.slot * (kFirst ? 2 : 1) * (size_t)p.I * p.H;
     // two weight rows per lane: (gate, up) of one h column, or two W2 rows 16 apart
@@ -76,7 +183,7 @@ __global__ __launch_bounds__(kFirst ? kThreads * kSplit1 : kThreads * kSplit2) v
     const uint16_t *wa = W + (size_t)ra * K, *wb = W + (size_t)rb * K;
     // token row of this lane (rows past the tile's end re-read its last row; their outputs are dropped)
     const int tr = mt.row_begin + min(n, mt.rows - 1);
-    const uint16_t *xr = (const uint16_t *)(kFirst ? p.x : p.h) + (size_t)(kFirst ? p.perm[tr] : tr) * K;
+    const uint16_t *xr = (const uint16_t *)(kFirst ? p.x : p.h) + (size_t)(kSelf ? self_token : kFirst ? p.perm[tr] : tr) * K;
 
     // this wavefront's K-chunks: [kbeg, kend)
     const int chunks = (K + 127) >> 7, per = (chunks + NS - 1) / NS;
@@ -139,12 +246,19 @@ __global__ __launch_bounds__(kFirst ? kThreads * kSplit1 : kThreads * kSplit2) v
 
 int decode_tile_rows() { return kTileRows; }
 
+// GEMM-1 can derive its tiles itself when the selection kernel left per-block masks for at most 4 blocks and 64 slots
+bool decode_self_tiles(const Pass &p)
+{
+    return p.fused_hist && p.S <= kSelfMaxSlots && p.T <= kSelfMaxBlocks * kFusedTokens && kSplit1 * kThreads >= 64;
+}
+
 hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st)
 {
     if (which == 0) {
         const int groups = (p.I + kWRows / 2 - 1) / (kWRows / 2);
         const int blocks = p.max_tiles * groups;
-        hipLaunchKernelGGL((k_expert_decode<true>), dim3(blocks), dim3(kThreads * kSplit1), 0, st, p);
+        if (p.self_tiles) hipLaunchKernelGGL((k_expert_decode<true, true>), dim3(blocks + 1), dim3(kThreads * kSplit1), 0, st, p);
+        else              hipLaunchKernelGGL((k_expert_decode<true>), dim3(blocks), dim3(kThreads * kSplit1), 0, st, p);
     } else {
         const int groups = (p.H + 16 * kBlocks2 - 1) / (16 * kBlocks2);
         const int blocks = p.max_tiles * groups;

@@ -145,6 +145,7 @@ struct moe_layer {
     long long prof_count = 0;  // forwards recorded since profiling was enabled
     long long prof_seen = 0;   // forwards issued since then
     int prof_every = 1;        // every prof_every-th forward is recorded
+    int prof_phase = -1;       // the one phase whose two events are recorded, or -1: all of them
     hipEvent_t ev[kProfRing][MOE_N_PHASES + 1] = {};
     moe_config_t cfg;
     moe_buffers_t buf;
@@ -298,6 +299,16 @@ moe_status_t moe_profile_enable(moe_layer_t *l, int32_t enable)
     return MOE_OK;
 }
 
+moe_status_t moe_profile_select(moe_layer_t *l, int32_t phase)
+{
+    if (!l) return fail(MOE_ERR_ARG, "layer is NULL");
+    if (phase < -1 || phase >= MOE_N_PHASES) return fail(MOE_ERR_ARG, "phase %d is outside [-1, %d)", phase, MOE_N_PHASES);
+    l->prof_phase = phase;
+    l->prof_count = 0;         // recordings made under another selection cannot be read as this one
+    l->prof_seen = 0;
+    return MOE_OK;
+}
+
 moe_status_t moe_profile_read(moe_layer_t *l, int32_t back, float *ms)
 {
     if (!l || !ms) return fail(MOE_ERR_ARG, "layer or ms is NULL");
@@ -305,9 +316,12 @@ moe_status_t moe_profile_read(moe_layer_t *l, int32_t back, float *ms)
     if (back < 0 || back >= kProfRing || back >= l->prof_count)
         return fail(MOE_ERR_ARG, "no recorded forward %d steps back (recorded %lld, kept %d)", back, l->prof_count, kProfRing);
     hipEvent_t *ev = l->ev[(l->prof_count - 1 - back) % kProfRing];
-    hipError_t e = hipEventSynchronize(ev[MOE_N_PHASES]);
+    const int sel = l->prof_phase;
+    hipError_t e = hipEventSynchronize(ev[sel < 0 ? MOE_N_PHASES : sel + 1]);
     if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
     for (int j = 0; j < MOE_N_PHASES; ++j) {
+        ms[j] = 0.f;
+        if (sel >= 0 && j != sel) continue;
         e = hipEventElapsedTime(&ms[j], ev[j], ev[j + 1]);
         if (e != hipSuccess) return fail(MOE_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
     }
@@ -600,11 +614,14 @@ static moe_status_t forward_pass(moe_layer_t *l, const void *x, int32_t T, const
     // optional phase events (benchmarks): event j is recorded before phase j, the last one after the pass
     hipEvent_t *ev = l->prof_on && l->prof_seen++ % l->prof_every == 0 ? l->ev[l->prof_count % kProfRing] : nullptr;
     hipError_t e = hipSuccess;
-    auto mark = [&](int j) { if (ev && e == hipSuccess) e = hipEventRecord(ev[j], st); };
+    const int sel = l->prof_phase;
+    auto mark = [&](int j) { if (ev && e == hipSuccess && (sel < 0 || j == sel || j == sel + 1)) e = hipEventRecord(ev[j], st); };
     mark(MOE_PHASE_GATE);
     if (e == hipSuccess && !routed_ids) e = launch_gate(p, st);
     mark(MOE_PHASE_PERMUTE);
-    if (e == hipSuccess) e = launch_permute(p, tile_rows, big, st);   // the large-tile kernels deal a size-ordered list round-robin to the XCDs
+    // few tokens, few slots: the weight-streaming GEMM-1 derives its tiles itself and writes the tables beside its stream
+    p.self_tiles = tiny && !identity && decode_self_tiles(p);
+    if (e == hipSuccess && !p.self_tiles) e = launch_permute(p, tile_rows, big, st);   // the large-tile kernels deal a size-ordered list round-robin to the XCDs
     mark(MOE_PHASE_GEMM1);
     if (e == hipSuccess) {
         if (identity)  e = launch_identity_experts(p, st);

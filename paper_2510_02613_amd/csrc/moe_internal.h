@@ -85,6 +85,8 @@ struct Pass {
     void *y;             // [A,H]
     int32_t max_tiles;
     int32_t gate_tiled;  // the LDS-tiled gate logits kernel is forced (testing aid)
+    int32_t self_tiles;  // weight-streaming GEMM-1 only: its workgroups derive their tile from the selection kernel's per-block counts and
+                         // masks themselves, and workgroup 0 of the launch writes the tables (offsets, permutation, tile list) beside them
     int32_t fused_hist;  // the selection kernel also ranks the assignments (blocks of kFusedTokens tokens, blk_hist [S][blocks]
                          // of token masks); the scan-and-place kernel finishes the bookkeeping
     float *partials;     // partial sums of the large-tile GEMMs' split tiles, or NULL (no room: never split)
@@ -123,6 +125,7 @@ hipError_t launch_ceiling_tile_stream(const void *buf, int n_tiles, size_t row_b
 // weight-streaming variant for decode-sized batches (M-tiles of 16 rows)
 hipError_t launch_experts_decode(const Pass &p, int which, hipStream_t st);
 int decode_tile_rows();
+bool decode_self_tiles(const Pass &p);   // GEMM-1 needs no bookkeeping kernel in front of it (Pass::self_tiles)
 hipError_t launch_identity_experts(const Pass &p, hipStream_t st);
 hipError_t launch_combine(const Pass &p, hipStream_t st);
 

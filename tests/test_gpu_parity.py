@@ -490,3 +490,31 @@ def test_shared_expert_tiles_share_an_xcd_on_the_dsv3_shape_small():
     assert v["counts"][16] == 1200 and (v["tiles"][:, 0] == 16).sum() == 4
     shares = check_units(case, v)
     assert shares == [1.0, 1.0], shares
+
+
+@pytest.mark.parametrize("tokens", [1, 7, 16, 17, 40, 64])
+@pytest.mark.parametrize("gate", ["softmax", "sigmoid_group"])
+def test_few_tokens_expert_kernels_derive_their_tiles(tokens, gate):
+    """Up to 64 tokens and 64 slots the weight-streaming GEMM-1 is launched without the offsets / permutation /
+    tile-list kernel in front of it: its workgroups derive their tile from the selection kernel's block masks
+    and one of them writes the tables.  Output and tables must match the oracle and -- bit for bit, on a
+    workspace whose scratch part was overwritten with NaN patterns before each pass -- the separate
+    bookkeeping kernels' pass, with remote experts, a shared expert on part of the batch and spare slots."""
+    import torch
+    from gpu_util import Case, tensor_to_host
+    from paper_2510_02613_amd import binding as B
+    kw = dict(n_group=4, topk_group=2, routed_scale=2.5) if gate == "sigmoid_group" else {}
+    wl = MoEWorkload(name="few", tokens=tokens, hidden=320, inter=136, n_experts=64, top_k=4, n_slots=23, n_local=20,
+                     act_dtype="bf16", router_dtype="bf16", gate=gate, n_shared=1, shared_range=(tokens // 2, tokens),
+                     seed=71 + tokens, **kw)
+    case = _case(wl)
+    out, v, _ = _full_check(case)
+    scratch = B.moe_workspace_view(case.layer.handle).topk_ids - case.layer.workspace.data_ptr()
+    runs = []
+    for flags in (0, B.MOE_FLAG_PERMUTE_UNFUSED, 0):
+        case.layer.workspace[scratch:].fill_(0xff)
+        runs.append((case.run(flags=flags), case.layer.view(tokens)))
+    for o, vv in runs:
+        np.testing.assert_array_equal(o, out)
+        for key in ("counts", "offsets", "perm", "inv", "tiles", "h", "y"):
+            np.testing.assert_array_equal(vv[key], v[key])
