@@ -276,9 +276,11 @@ __device__ void deal_units_grouped(const Pass &p, const MTile *src, const int32_
 {
     constexpr int HT = NT / 2;
     __shared__ int32_t colF_all[2][8];   // units at the head of every column that belong to pieces
+    __shared__ int32_t colC_all[2][8];   // whole single tiles a column has room for on top of them
     const int which = (int)threadIdx.x / HT, t = (int)threadIdx.x % HT;
     int32_t *tmp = tmp_all + which * (kSortMax / 2);
     int32_t *colF = colF_all[which];
+    int32_t *cap = colC_all[which];
     const int ns = p.n_slices[which];
     const int runs = mfma8_runs(n, ns), spp = ns / runs;
     const int total = n * runs;
@@ -315,7 +317,8 @@ __device__ void deal_units_grouped(const Pass &p, const MTile *src, const int32_
         }
         carry += tot;
     }
-    const int P = (int)(carry >> 32), R = (int)(carry & 0xffffffffu);
+    const int P = (int)(carry >> 32);
+    int R = (int)(carry & 0xffffffffu);                     // single units (later: those dealt unit by unit)
     __syncthreads();
     // piece k sits in column k mod 8 behind the earlier pieces of that column
     if (ok) {
@@ -332,6 +335,46 @@ __device__ void deal_units_grouped(const Pass &p, const MTile *src, const int32_
 #pragma unroll
     for (int x = 0; x < 8; ++x) { F[x] = colF[x]; Fmax = max(Fmax, F[x]); }
     const bool grouped = ok && Fmax <= limit;               // uniform over the half
+    // Single tiles come in `runs` units each.  As long as whole tiles fit under the even column height, a tile's
+    // runs stay in ONE column, one behind the other (its token rows are then fetched by one XCD): tile j of the
+    // first NA single tiles goes to block level k -- the k-th tile on top of a column's pieces -- of the columns
+    // that have room for it, level by level; what is left of the single tiles is dealt unit by unit as before.
+    int capsum = 0, capmax = 0;
+    {
+        int U = R;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) U += F[x];
+        const int even = U / 8;
+        if (t < 8) cap[t] = runs > 1 ? max(0, (even - colF[t]) / runs) : 0;   // kept in LDS: registers are scarce here
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            capsum += cap[x];
+            capmax = max(capmax, cap[x]);
+        }
+    }
+    const int NA = min(R / runs, capsum);                   // single tiles kept whole
+    auto belowA = [&](int k) { int c = 0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) c += min(cap[x], k);
+        return c; };
+    auto levelA = [&](int j) {                              // the largest k with belowA(k) <= j  (j < capsum)
+        int lo = 0, hi = capmax + 1;
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (belowA(mid) <= j) lo = mid; else hi = mid; }
+        return lo; };
+    if (NA > 0) {                                           // column heights with the whole tiles on top of the pieces
+        const int kL = levelA(NA - 1), lastn = NA - belowA(kL);
+        int rank = 0;
+        Fmax = 0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            int used = min(cap[x], kL);
+            if (cap[x] > kL) { if (rank < lastn) ++used; ++rank; }
+            F[x] += used * runs;
+            Fmax = max(Fmax, F[x]);
+        }
+    }
+    R -= NA * runs;                                         // the single units that are dealt one by one
     // level of single unit i: the largest l with C(l) <= i, C(l) = sum over columns of max(0, l - F[x]) = single units below level l
     auto below = [&](int l) { int c = 0;
 #pragma unroll
@@ -391,8 +434,21 @@ __device__ void deal_units_grouped(const Pass &p, const MTile *src, const int32_
         const int i0 = (int)(carry2 + half_exclusive_scan_u64<NT>((unsigned long long)(has * runs), scratch, &tot));
         if (has && grouped) {
             const MTile tl = src[order[gq0[g] + m - 1]];      // the group's last tile
+            const int j = i0 / runs;                         // its number among the single tiles
+            if (j < NA) {                                    // whole: block level k of the rank-th column that reaches it
+                const int k = levelA(j), rank = j - belowA(k);
+                int x = 0, base = 0;
+#pragma unroll
+                for (int xx = 7; xx >= 0; --xx) {
+                    int before = 0;
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) before += (y < xx && cap[y] > k);
+                    if (cap[xx] > k && before == rank) { x = xx; base = colF[xx]; }   // the column's pieces end there
+                }
+                for (int r = 0; r < runs; ++r) put(base + k * runs + r, x, tl, r);
+            } else
             for (int r = 0; r < runs; ++r) {
-                const int i = i0 + r, l = level_of(i);
+                const int i = i0 - NA * runs + r, l = level_of(i);
                 const int rank = i - below(l);
                 int x = 0;
 #pragma unroll

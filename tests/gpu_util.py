@@ -221,12 +221,13 @@ def check_bookkeeping(case: Case, v: dict, T: int, shared_range, flags=0):
         check_units(case, v)
 
 
-def check_units(case: Case, v: dict):
+def check_units(case: Case, v: dict, whole=None):
     """The work-unit lists of the large-tile kernels (call after a pass that ran them): per GEMM, every N-slice
     of every tile is in exactly one unit, holes only at the ends of the eight columns, columns differ by at most
     a few units, and the tiles of a slot that sit together in the tile list share a column when the pass has
     such groups.  Returns, per GEMM, the share of the avoidable weight fetches (tiles - 1 per multi-tile slot and
-    size) that the columns avoid."""
+    size) that the columns avoid; whole (a list) receives, per GEMM, the share of the single tiles whose runs sit
+    in one column."""
     wl = case.wl
     tiles, hdr, lists = v["tiles"], v["unit_hdr"], v["units"]
     n_slices = ((wl.inter + 127) // 128, (wl.hidden + 255) // 256)
@@ -261,6 +262,15 @@ def check_units(case: Case, v: dict):
         # of the weight fetches that sharing a column can save (tiles - 1 per group), the share that is saved
         # (tiles - columns used); groups larger than half a column are cut on purpose
         shares.append(sum(sizes[k] - len(groups[k]) for k in multi) / sum(sizes[k] - 1 for k in multi) if multi else None)
+        if whole is not None:
+            # of the tiles that are alone in their slot, the share whose runs all sit in ONE column (their token
+            # rows are then fetched by one XCD); None when tiles are not split into runs
+            per_tile = {}
+            for i in np.nonzero(live)[0]:
+                slot, r0, rows, info = u[i]
+                per_tile.setdefault((int(slot), int(r0)), set()).add(int(cols[i]))
+            alone = [k for k in per_tile if sum(1 for q in per_tile if q[0] == k[0]) == 1]
+            whole.append(sum(len(per_tile[k]) == 1 for k in alone) / len(alone) if runs > 1 and alone else None)
     return shares
 
 

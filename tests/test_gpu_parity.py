@@ -488,8 +488,12 @@ def test_shared_expert_tiles_share_an_xcd_on_the_dsv3_shape_small():
     case = _case(wl)
     _, v, _ = _full_check(case)
     assert v["counts"][16] == 1200 and (v["tiles"][:, 0] == 16).sum() == 4
-    shares = check_units(case, v)
+    whole = []
+    shares = check_units(case, v, whole)
     assert shares == [1.0, 1.0], shares
+    # every tile is two runs of N-slices here: the single tiles that fit under the even column height keep both
+    # runs on one XCD (12 of 16), the rest even the columns out unit by unit
+    assert all(w is not None and w >= 0.7 for w in whole), whole
 
 
 @pytest.mark.parametrize("tokens", [1, 7, 16, 17, 40, 64])
