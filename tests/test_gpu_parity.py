@@ -246,6 +246,23 @@ def test_phase_timing_reports_every_phase():
         assert sum(B.moe_profile_read(case.layer.handle, back)) > 0
     with pytest.raises(B.MoEError):
         B.moe_profile_read(case.layer.handle, 6)
+    # one phase only: two events per recorded forward, the other phases read 0; earlier recordings are forgotten
+    gemm1 = B.PHASE_NAMES.index("gemm1")
+    B.moe_profile_select(case.layer.handle, gemm1)
+    with pytest.raises(B.MoEError):
+        B.moe_profile_read(case.layer.handle, 0)
+    B.moe_profile_enable(case.layer.handle, 1)
+    for _ in range(2):
+        case.run()
+    for back in range(2):
+        ms = B.moe_profile_read(case.layer.handle, back)
+        assert 0 < ms[gemm1] < 1000 and all(v == 0 for i, v in enumerate(ms) if i != gemm1)
+    for bad in (-2, 5):
+        with pytest.raises(B.MoEError):
+            B.moe_profile_select(case.layer.handle, bad)
+    B.moe_profile_select(case.layer.handle, -1)
+    case.run()
+    assert all(v > 0 for v in B.moe_profile_read(case.layer.handle, 0))
     B.moe_profile_enable(case.layer.handle, 0)
     _full_check(case)
 
