@@ -539,3 +539,20 @@ def test_few_tokens_expert_kernels_derive_their_tiles(tokens, gate):
         np.testing.assert_array_equal(o, out)
         for key in ("counts", "offsets", "perm", "inv", "tiles", "h", "y"):
             np.testing.assert_array_equal(vv[key], v[key])
+
+
+def test_ceiling_kernels_run():
+    """The measuring-stick kernels of the benchmark (register-only MFMA loop, plain read, read in the large-tile
+    kernels' weight-copy shape) run on small buffers and leave them untouched."""
+    import torch
+    from paper_2510_02613_amd import binding as B
+    buf = torch.arange(6 * 256 * 512 // 4, dtype=torch.int32, device="cuda:0")   # 6 tiles of 256 rows x 512 bytes
+    before = buf.clone()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    s = torch.cuda.current_stream().cuda_stream
+    assert B.moe_ceiling_mfma(64, 100, True, sink.data_ptr(), s) > 0
+    B.moe_ceiling_stream(buf.data_ptr(), buf.numel() * 4, sink.data_ptr(), s)
+    for nt in (False, True):
+        B.moe_ceiling_tile_stream(buf.data_ptr(), 6, 512, nt, s)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
