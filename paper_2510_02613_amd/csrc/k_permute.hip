@@ -621,13 +621,15 @@ __global__ __launch_bounds__(kThreads) void k_slot_scan(Pass p, int n_blocks, in
     offsets_and_tiles<kThreads>(p, tile_rows, sort_tiles && p.max_tiles <= kSortMax, cnt, fkey);
 }
 
-// Second and last kernel of the fused bookkeeping (after k_gate_select_hist).  Workgroup b < n_blocks
-// places the assignments of tokens [16 b, 16 b + 16); workgroup n_blocks writes counts, offsets and the
-// tile list.  Nobody waits for anybody: every workgroup adds up, for itself, the block masks of all
-// slots (a wavefront per slot, 64 blocks per load, wavefront reductions) -- rows per slot in the whole
+// Second and last kernel of the fused bookkeeping (after k_gate_select_hist).  Workgroup 0 writes counts,
+// offsets, the tile list and the unit lists; workgroup b + 1, b < n_blocks, places the assignments of tokens
+// [16 b, 16 b + 16).  Nobody waits for anybody: every workgroup adds up, for itself, the block masks of all
+// slots (a quarter wavefront per slot, row-wise reductions) -- rows per slot in the whole
 // pass and in the blocks before its own -- and scans the totals; at most 512 blocks x S words, out of L2.
-// 64 registers at most: two workgroups of 16 wavefronts per compute unit, so that all workgroups of a pass of up to 8192
-// tokens run at once (the tile list's workgroup is the last one of the grid)
+// 64 registers at most: two workgroups of 16 wavefronts per compute unit, 512 on the chip.  The tile list's
+// workgroup is the longest of the launch (2 to 3 times a placing one) and therefore the first of the grid: at
+// 8192 tokens the launch has 513 workgroups, and the one that has to wait for a place should be a short one
+// (measured at 8192 tokens: the kernel 3 us shorter than with the tile list's workgroup last).
 __global__ __launch_bounds__(kFusedTokens * 64) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_scan_place(Pass p, int n_blocks, int tile_rows, int sort_tiles)
 {
     constexpr int NT = kFusedTokens * 64;
@@ -635,8 +637,9 @@ __global__ __launch_bounds__(kFusedTokens * 64) __attribute__((amdgpu_waves_per_
     __shared__ int32_t base[kMaxSlots];    // rows of the slot in earlier blocks; the tile workgroup: the group's first-assignment key
     __shared__ int32_t scratch[NT / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int S = p.S, b = blockIdx.x;
-    const bool tiles_wg = b == n_blocks;
+    const int S = p.S;
+    const bool tiles_wg = blockIdx.x == 0;
+    const int b = tiles_wg ? n_blocks : (int)blockIdx.x - 1;
     // Every workgroup of the launch adds up the rows per (slot, block) of the whole pass, so this loop is the
     // kernel.  The counts are bytes (at most 16 rows of a slot per block), blk_cnt [S][row_stride]: a quarter
     // wavefront owns a slot (four slots per wavefront and round), lane `sub` of the 16 the bytes of blocks
