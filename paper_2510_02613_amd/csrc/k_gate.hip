@@ -68,9 +68,10 @@ __device__ int select_token(const Pass &p, int t, float *lg, float *cs, float *g
         // L lanes share a group's experts (L a power of two, G * L <= 64): each finds the two largest
         // of its share, then the pairs are merged across the L lanes -- a group's score is the sum of
         // its two largest selection scores, which does not depend on the order they are found in
-        int L = 1;
-        while (2 * L * G <= 64) L *= 2;
-        const int g = lane / L, sub = lane - g * L;
+        int Lsh = 0;
+        while ((2 * G) << Lsh <= 64) ++Lsh;
+        const int L = 1 << Lsh;
+        const int g = lane >> Lsh, sub = lane & (L - 1);
         float b1 = NEG, b2 = NEG;
         if (g < G) {
             for (int e = g * per + sub; e < (g + 1) * per; e += L) {
@@ -83,19 +84,22 @@ __device__ int select_token(const Pass &p, int t, float *lg, float *cs, float *g
             b2 = fmaxf(fminf(b1, o1), fmaxf(b2, o2));
             b1 = fmaxf(b1, o1);
         }
-        const float gs = (per > 1) ? b1 + b2 : b1;
-        const bool head = g < G && sub == 0;     // the lane that speaks for group g
-        // pick topk_group groups; a group's head lane remembers whether it was kept
-        bool kept = false;
-        for (int r = 0; r < p.topk_group; ++r) {
-            unsigned long long key = (head && !kept) ? make_key(gs, g) : 0ull;
-            int win = key_index(wave_max_u64(key));
-            if (head && g == win) kept = true;
+        // every lane of a group now holds the group's score.  The topk_group best groups are kept, the lower
+        // index first among equal scores: a group's rank is the number of groups that come before it in that
+        // order (the scores of all groups are read lane by lane), and it is kept when its rank is below topk_group
+        const uint32_t mine = orderable((per > 1) ? b1 + b2 : b1);
+        int rank = 0;
+        for (int h = 0; h < G; ++h) {
+            const uint32_t other = (uint32_t)__builtin_amdgcn_readlane((int)mine, h << Lsh);
+            rank += (other > mine || (other == mine && h < g)) ? 1 : 0;
         }
-        if (head) gsc[g] = kept ? 1.f : 0.f;
-        wave_sync();
-        for (int e = lane; e < E; e += 64)
-            if (gsc[e / per] == 0.f) cs[e] = NEG;
+        const unsigned long long keptmask = __ballot(g < G && rank < p.topk_group);   // bit g L: group g is kept
+        const bool pow2 = (per & (per - 1)) == 0;
+        const int psh = 31 - __clz(per);
+        for (int e = lane; e < E; e += 64) {
+            const int ge = pow2 ? e >> psh : e / per;
+            if (!((keptmask >> (ge << Lsh)) & 1ull)) cs[e] = NEG;
+        }
         wave_sync();
     }
     // top-k by repeated wavefront arg-max
