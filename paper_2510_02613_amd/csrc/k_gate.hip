@@ -42,9 +42,8 @@ __device__ __forceinline__ int key_index(unsigned long long key) { return (int)(
 // Phase 2 for one token, run by one wavefront.
 //   lg   : LDS [E] logits in, scores out
 //   cs   : LDS [E] selection scores (biased), destroyed (taken entries -> -inf)
-//   gsc  : LDS [n_group] group scores
 // Returns the expert this lane holds (lane j < k: the j-th selected), which is also written to p.ids.
-__device__ int select_token(const Pass &p, int t, float *lg, float *cs, float *gsc, int lane)
+__device__ int select_token(const Pass &p, int t, float *lg, float *cs, int lane)
 {
     const int E = p.E;
     const float NEG = -__builtin_huge_valf();
@@ -180,7 +179,6 @@ __global__ __launch_bounds__(kThreads) void k_gate(Pass p)
     float *ws = xs + kTokens * kKC;          // [kET][kKC+1]
     float *lg = ws + kET * (kKC + 1);        // [kTokens][E]
     float *cs = lg + kTokens * p.E;          // [4 waves][E]
-    float *gsc = cs + 4 * p.E;               // [4 waves][64]
 
     const int tid = threadIdx.x;
     const int t0 = blockIdx.x * kTokens;
@@ -228,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void k_gate(Pass p)
     const int wave = tid >> 6, lane = tid & 63;
     for (int tt = wave; tt < kTokens; tt += 4) {
         int t = t0 + tt;
-        if (t < p.T) select_token(p, t, lg + tt * E, cs + wave * E, gsc + wave * 64, lane);
+        if (t < p.T) select_token(p, t, lg + tt * E, cs + wave * E, lane);
     }
 }
 
@@ -569,9 +567,8 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
     extern __shared__ float smem[];
     const int E = p.E;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *lg = smem + wave * (2 * E + 64);   // [E] logits -> scores
+    float *lg = smem + wave * 2 * E;         // [E] logits -> scores
     float *cs = lg + E;                       // [E] selection scores
-    float *gsc = cs + E;                      // [64]
     const int t = blockIdx.x * 4 + wave;
     if (t >= p.T) return;
     for (int e = lane; e < E; e += 64) {
@@ -586,7 +583,7 @@ __global__ __launch_bounds__(kThreads) void k_gate_select(Pass p)
         lg[e] = v;
     }
     wave_sync();
-    select_token(p, t, lg, cs, gsc, lane);
+    select_token(p, t, lg, cs, lane);
 }
 
 // The selection kernel with the first step of the routing bookkeeping fused in: a workgroup of 16
@@ -603,10 +600,9 @@ __global__ __launch_bounds__(kFusedTokens * 64) void k_gate_select_hist(Pass p, 
     extern __shared__ float smem[];
     const int E = p.E, S = p.S;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *lg = smem + wave * (2 * E + 64);   // [E] logits -> scores
+    float *lg = smem + wave * 2 * E;         // [E] logits -> scores
     float *cs = lg + E;                       // [E] selection scores
-    float *gsc = cs + E;                      // [64]
-    uint32_t *blkmask = (uint32_t *)(smem + kFusedTokens * (2 * E + 64));   // [S]
+    uint32_t *blkmask = (uint32_t *)(smem + kFusedTokens * 2 * E);   // [S]
     for (int s = threadIdx.x; s < S; s += kFusedTokens * 64) blkmask[s] = 0u;
     const int t = blockIdx.x * kFusedTokens + wave;
     int slot = -1;
@@ -623,7 +619,7 @@ __global__ __launch_bounds__(kFusedTokens * 64) void k_gate_select_hist(Pass p, 
             lg[e] = v;
         }
         wave_sync();
-        const int id = select_token(p, t, lg, cs, gsc, lane);
+        const int id = select_token(p, t, lg, cs, lane);
         if (lane < p.k) {
             const int m = p.map[id];
             if (m >= -1) {
@@ -686,7 +682,7 @@ hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
     p.logit_planes = planes;
     if (p.fused_hist) {
         const int nb = (p.T + kFusedTokens - 1) / kFusedTokens;
-        const size_t smem = sizeof(float) * kFusedTokens * (2 * (size_t)p.E + 64) + sizeof(uint32_t) * p.S;
+        const size_t smem = sizeof(float) * kFusedTokens * 2 * (size_t)p.E + sizeof(uint32_t) * p.S;
         if (smem > 64 * 1024) {
             e = hipFuncSetAttribute((const void *)k_gate_select_hist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
@@ -694,7 +690,7 @@ hipError_t launch_gate_mfma(const Pass &p0, hipStream_t st)
         hipLaunchKernelGGL(k_gate_select_hist, dim3(nb), dim3(kFusedTokens * 64), smem, st, p, nb);
         return hipGetLastError();
     }
-    const size_t smem = sizeof(float) * 4 * (2 * (size_t)p.E + 64);
+    const size_t smem = sizeof(float) * 4 * 2 * (size_t)p.E;
     hipLaunchKernelGGL(k_gate_select, dim3((p.T + 3) / 4), dim3(kThreads), smem, st, p);
     return hipGetLastError();
 }
@@ -705,7 +701,7 @@ hipError_t launch_gate(const Pass &p, hipStream_t st)
 {
     if (p.act_bf16) return p.router_bf16 ? launch_gate_mfma<uint16_t>(p, st) : launch_gate_mfma<float>(p, st);
     const int blocks = (p.T + kTokens - 1) / kTokens;
-    const size_t smem = sizeof(float) * (kTokens * kKC + kET * (kKC + 1) + (size_t)kTokens * p.E + 4 * (size_t)p.E + 4 * 64);
+    const size_t smem = sizeof(float) * (kTokens * kKC + kET * (kKC + 1) + (size_t)kTokens * p.E + 4 * (size_t)p.E);
     dim3 grid(blocks), block(kThreads);
     if (smem > 64 * 1024) {  // opt in to the large-LDS launch once per kernel variant is cheap enough
         hipError_t e = hipSuccess;
