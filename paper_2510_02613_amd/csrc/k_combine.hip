@@ -23,62 +23,103 @@ template <typename T> struct Chunk;
 template <> struct Chunk<uint16_t> { static constexpr int n = 8; };  // 8 bf16 = 16 B
 template <> struct Chunk<float> { static constexpr int n = 4; };     // 4 fp32 = 16 B
 
-template <typename T, bool kBatched>
+// kChunks: 0 = few tokens (see below), else the column chunks a thread works on at once
+template <typename T, int kChunks>
 __global__ __launch_bounds__(256) void k_combine(Pass p)
 {
     constexpr int C = Chunk<T>::n;
     __shared__ int32_t rows[kMaxKK];
     __shared__ float wts[kMaxKK];
+    __shared__ int32_t n_local;
     const int t = blockIdx.x;
-    if (threadIdx.x < p.kk) {
+    if (threadIdx.x < 64) {   // first wavefront: the token's local assignments, compacted, still in selection order
         const int j = threadIdx.x;
-        rows[j] = p.inv[(size_t)t * p.kk + j];
-        wts[j] = j < p.k ? p.w[(size_t)t * p.k + j] : 1.0f;
+        int r = -1;
+        float wv = 0.f;
+        if (j < p.kk) {
+            r = p.inv[(size_t)t * p.kk + j];
+            wv = j < p.k ? p.w[(size_t)t * p.k + j] : 1.0f;
+        }
+        const unsigned long long m = __ballot(r >= 0);
+        if (r >= 0) {
+            const int at = __popcll(m & ((1ull << j) - 1ull));
+            rows[at] = r;
+            wts[at] = wv;
+        }
+        if (j == 0) n_local = __popcll(m);
     }
     __syncthreads();
+    const int n = n_local;
     const T *y = (const T *)p.y;
     T *out = (T *)p.out + (size_t)t * p.H;
-    for (int c = (blockIdx.y * 256 + threadIdx.x) * C; c < p.H; c += gridDim.y * 256 * C) {
-    float acc[C];
-#pragma unroll
-    for (int i = 0; i < C; ++i) acc[i] = 0.f;
-    if (kBatched) {
+    const int stride = gridDim.y * 256 * C;
+    if (kChunks == 0) {
         // few tokens: the rows of four assignments are requested before any is added (the loads are
         // independent, only the additions are ordered), since there is no other workgroup to hide them
-        for (int j0 = 0; j0 < p.kk; j0 += 4) {
-            uint4 raw[4];
-            float wj[4];
+        for (int c = (blockIdx.y * 256 + threadIdx.x) * C; c < p.H; c += stride) {
+            float acc[C];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = j0 + u < p.kk ? rows[j0 + u] : -1;
-                // an assignment that is not local contributes weight 0 times zeros (nothing is read for it)
-                raw[u] = make_uint4(0, 0, 0, 0);
-                if (r >= 0) raw[u] = *(const uint4 *)(y + (size_t)r * p.H + c);
-                wj[u] = r < 0 ? 0.f : wts[j0 + u];
+            for (int i = 0; i < C; ++i) acc[i] = 0.f;
+            for (int j0 = 0; j0 < n; j0 += 4) {
+                uint4 raw[4];
+                float wj[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // past the last local assignment: weight 0 times zeros (nothing is read)
+                    raw[u] = make_uint4(0, 0, 0, 0);
+                    if (j0 + u < n) raw[u] = *(const uint4 *)(y + (size_t)rows[j0 + u] * p.H + c);
+                    wj[u] = j0 + u < n ? wts[j0 + u] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const T *v = (const T *)&raw[u];
+#pragma unroll
+                    for (int i = 0; i < C; ++i) acc[i] = fmaf(wj[u], load_f32<T>(v, i), acc[i]);
+                }
             }
+            uint4 o;
+            T *ov = (T *)&o;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const T *v = (const T *)&raw[u];
-#pragma unroll
-                for (int i = 0; i < C; ++i) acc[i] = fmaf(wj[u], load_f32<T>(v, i), acc[i]);
-            }
+            for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[i]);
+            *(uint4 *)(out + c) = o;
         }
     } else {
-        for (int j = 0; j < p.kk; ++j) {
-            const int r = rows[j];
-            if (r < 0) continue;
-            const float wj = wts[j];
-            const uint4 raw = *(const uint4 *)(y + (size_t)r * p.H + c);
-            const T *v = (const T *)&raw;
+        // many tokens: a thread works on all (up to four) of its column chunks at once, so that as many loads of
+        // a row are in flight per thread (a token has one or two local assignments when the experts are spread
+        // over ranks, and the other workgroups of the compute unit do not cover the latency alone)
+        constexpr int U = kChunks > 0 ? kChunks : 1;
+        for (int c0 = (blockIdx.y * 256 + threadIdx.x) * C; c0 < p.H; c0 += U * stride) {
+            float acc[U][C];
 #pragma unroll
-            for (int i = 0; i < C; ++i) acc[i] = fmaf(wj, load_f32<T>(v, i), acc[i]);
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < C; ++i) acc[u][i] = 0.f;
+            for (int j = 0; j < n; ++j) {
+                const T *yr = y + (size_t)rows[j] * p.H;
+                const float wj = wts[j];
+                uint4 raw[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    raw[u] = make_uint4(0, 0, 0, 0);
+                    if (c0 + u * stride < p.H) raw[u] = *(const uint4 *)(yr + c0 + u * stride);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const T *v = (const T *)&raw[u];
+#pragma unroll
+                    for (int i = 0; i < C; ++i) acc[u][i] = fmaf(wj, load_f32<T>(v, i), acc[u][i]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (c0 + u * stride >= p.H) continue;
+                uint4 o;
+                T *ov = (T *)&o;
+#pragma unroll
+                for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[u][i]);
+                *(uint4 *)(out + c0 + u * stride) = o;
+            }
         }
-    }
-    uint4 o;
-    T *ov = (T *)&o;
-#pragma unroll
-    for (int i = 0; i < C; ++i) store_f32<T>(ov, i, acc[i]);
-    *(uint4 *)(out + c) = o;
     }
 }
 
@@ -112,12 +153,15 @@ hipError_t launch_combine(const Pass &p, hipStream_t st)
     const int per = 256 * (p.act_bf16 ? 8 : 4);
     const int ny = p.T >= 1024 ? 1 : (p.H + per - 1) / per;
     const bool few = p.T < 1024;
+    const bool wide = p.H > per;       // a thread has several chunks of the row
     if (p.act_bf16) {
-        if (few) hipLaunchKernelGGL((k_combine<uint16_t, true>), dim3(p.T, ny), dim3(256), 0, st, p);
-        else     hipLaunchKernelGGL((k_combine<uint16_t, false>), dim3(p.T, ny), dim3(256), 0, st, p);
+        if (few)       hipLaunchKernelGGL((k_combine<uint16_t, 0>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else if (wide) hipLaunchKernelGGL((k_combine<uint16_t, 4>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else           hipLaunchKernelGGL((k_combine<uint16_t, 1>), dim3(p.T, ny), dim3(256), 0, st, p);
     } else {
-        if (few) hipLaunchKernelGGL((k_combine<float, true>), dim3(p.T, ny), dim3(256), 0, st, p);
-        else     hipLaunchKernelGGL((k_combine<float, false>), dim3(p.T, ny), dim3(256), 0, st, p);
+        if (few)       hipLaunchKernelGGL((k_combine<float, 0>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else if (wide) hipLaunchKernelGGL((k_combine<float, 4>), dim3(p.T, ny), dim3(256), 0, st, p);
+        else           hipLaunchKernelGGL((k_combine<float, 1>), dim3(p.T, ny), dim3(256), 0, st, p);
     }
     return hipGetLastError();
 }
