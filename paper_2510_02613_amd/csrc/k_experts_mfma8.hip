@@ -275,13 +275,60 @@ __device__ __forceinline__ float *partial_at(float *set, int wave, int a, int t,
     return set + ((((wave * kWT + a) * kTC + t) * 4 + r4) * 64 + lane) * 4;   // 16 bytes per lane, 1 KB per instruction
 }
 
+// Epilogue of one token tile of a wavefront: accumulators (token tile t of the wavefront, its kWT weight
+// tiles) -> the wavefront's private LDS region [token row][column] -> coalesced rows of h (with SwiGLU) or y.
+template <bool kFirst>
+__device__ __forceinline__ void emit_token_tile(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, char *ring, int t,
+                                                const f32x16 (&v)[kWT])
+{
+    constexpr int COLS = kFirst ? kWT * 16 : kWT * 32;      // output columns of this wavefront
+    constexpr int STRIDE = kFirst ? kEpiStride1 : kEpiStride2;
+    char *mine = ring + c.wave * kEpiBytes;
+    const int l31 = c.lane & 31, khalf = c.lane >> 5;
+    constexpr int LPR = COLS / 4;                           // copy out: 8 bytes per lane, LPR lanes per row,
+    constexpr int RPI = 64 / LPR;                           // 64/LPR rows per instruction
+    uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y);
+    const int ncol0 = n0 + c.wn * COLS;
+    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
+    char *row = mine + l31 * STRIDE;
+#pragma unroll
+    for (int a = 0; a < kWT; ++a) {
+        constexpr int Q = kFirst ? 2 : 4;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            uint16_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float g = v[a][q * 4 + e];
+                if (kFirst) {
+                    const float u = v[a][(q + 2) * 4 + e];
+                    g = silu_mul(g, u);
+                }
+                o[e] = f32_to_bf16(g);
+            }
+            const int col = a * (kFirst ? 16 : 32) + q * 8 + khalf * 4;
+            *(uint2 *)(row + col * 2) = make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+        }
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPI) {
+        const int rr = r0 + lr;                       // row inside the token tile
+        const int m = (2 * t + c.wm) * 32 + rr;       // row inside the chunk
+        const uint2 w = *(const uint2 *)(mine + rr * STRIDE + lc * 2);
+        if (m < mt.rows && ncol0 + lc < N)
+            *(uint2 *)(O + (size_t)(mt.row_begin + m) * N + ncol0 + lc) = w;
+    }
+    wave_lds_sync();  // the region is rewritten by the next token tile
+}
+
 // kPhase 0: a whole tile.  1: the partial sums of one of n_parts K ranges of a tile, left in
-// p.partials.  2: the sum of a tile's partial sums, in K order, then the same epilogue as phase 0.
+// p.partials (phase 2, sum_body below, adds them up).
 // (Letting the last of a tile's workgroups to finish do the adding, in the same launch, was
 // measured and is slower: the device-wide fence it needs costs more than the third launch.)
 template <bool kFirst, int NTC, int kPhase>
 __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, int KT, char *ring,
-                                          float *tile_sets, int part, int n_parts, int tsel)
+                                          float *tile_sets, int part)
 {
     f32x16 acc[kWT][kTC];
 #pragma unroll
@@ -290,10 +337,8 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
         for (int t = 0; t < kTC; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
-    if (kPhase != 2) {
-        k_loop<NTC>(c, ring, KT, acc);
-        __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
-    }
+    k_loop<NTC>(c, ring, KT, acc);
+    __syncthreads();  // all operand reads are done: the ring becomes the epilogue staging area
     if (kPhase == 1) {
         float *mine = tile_sets + (size_t)part * kPartialFloats;
 #pragma unroll
@@ -307,66 +352,52 @@ __device__ __forceinline__ void wave_body(const Pass &p, const WaveCtx &c, const
                 }
         return;
     }
-    if (kPhase == 2) {
-        for (int q = 0; q < n_parts; ++q) {
-            float *set = tile_sets + (size_t)q * kPartialFloats;
+#pragma unroll
+    for (int t = 0; t < NTC; ++t) {
+        f32x16 v[kWT];
+#pragma unroll
+        for (int a = 0; a < kWT; ++a) v[a] = acc[a][t];
+        emit_token_tile<kFirst>(p, c, mt, n0, N, ring, t, v);
+    }
+}
+
+// Phase 2: the sum of a tile's partial sums, in K order, for token tile t of this wavefront, then the
+// same epilogue as a whole tile.  The sets of four parts are requested together (32 loads of 16 bytes
+// per lane in flight: the launch is one round of the chip, its length is that of one workgroup) and
+// added one after the other.
+template <bool kFirst>
+__device__ __forceinline__ void sum_body(const Pass &p, const WaveCtx &c, const MTile &mt, int n0, int N, char *ring,
+                                         float *tile_sets, int n_parts, int t)
+{
+    f32x16 s[kWT];
+#pragma unroll
+    for (int a = 0; a < kWT; ++a)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
+    for (int q0 = 0; q0 < n_parts; q0 += 4) {
+        float4 v[4][kWT][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (q0 + u >= n_parts) continue;               // uniform
+            float *set = tile_sets + (size_t)(q0 + u) * kPartialFloats;
 #pragma unroll
             for (int a = 0; a < kWT; ++a)
 #pragma unroll
-                for (int t = 0; t < NTC; ++t)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        if (t != tsel) continue;
-                        const float4 v = *(const float4 *)partial_at(set, c.wave, a, t, r4, c.lane);
-                        acc[a][t][r4 * 4] += v.x; acc[a][t][r4 * 4 + 1] += v.y; acc[a][t][r4 * 4 + 2] += v.z; acc[a][t][r4 * 4 + 3] += v.w;
-                    }
+                for (int r4 = 0; r4 < 4; ++r4) v[u][a][r4] = *(const float4 *)partial_at(set, c.wave, a, t, r4, c.lane);
         }
-    }
-
-    // ---- epilogue: accumulators -> private LDS region [token row][column] -> coalesced rows ----
-    constexpr int COLS = kFirst ? kWT * 16 : kWT * 32;      // output columns of this wavefront
-    constexpr int STRIDE = kFirst ? kEpiStride1 : kEpiStride2;
-    char *mine = ring + c.wave * kEpiBytes;
-    const int l31 = c.lane & 31, khalf = c.lane >> 5;
-    constexpr int LPR = COLS / 4;                           // copy out: 8 bytes per lane, LPR lanes per row,
-    constexpr int RPI = 64 / LPR;                           // 64/LPR rows per instruction
-    uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y);
-    const int ncol0 = n0 + c.wn * COLS;
-    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
 #pragma unroll
-    for (int t = 0; t < NTC; ++t) {
-        if (kPhase == 2 && t != tsel) continue;   // phase 2: one token tile per wavefront and workgroup
-        char *row = mine + l31 * STRIDE;
+        for (int u = 0; u < 4; ++u) {
+            if (q0 + u >= n_parts) continue;
 #pragma unroll
-        for (int a = 0; a < kWT; ++a) {
-            constexpr int Q = kFirst ? 2 : 4;
+            for (int a = 0; a < kWT; ++a)
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                uint16_t v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float g = acc[a][t][q * 4 + e];
-                    if (kFirst) {
-                        const float u = acc[a][t][(q + 2) * 4 + e];
-                        g = silu_mul(g, u);
-                    }
-                    v[e] = f32_to_bf16(g);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    s[a][r4 * 4] += v[u][a][r4].x; s[a][r4 * 4 + 1] += v[u][a][r4].y;
+                    s[a][r4 * 4 + 2] += v[u][a][r4].z; s[a][r4 * 4 + 3] += v[u][a][r4].w;
                 }
-                const int col = a * (kFirst ? 16 : 32) + q * 8 + khalf * 4;
-                *(uint2 *)(row + col * 2) = make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
-            }
         }
-        wave_lds_sync();
-#pragma unroll
-        for (int r0 = 0; r0 < 32; r0 += RPI) {
-            const int rr = r0 + lr;                       // row inside the token tile
-            const int m = (2 * t + c.wm) * 32 + rr;       // row inside the chunk
-            const uint2 v = *(const uint2 *)(mine + rr * STRIDE + lc * 2);
-            if (m < mt.rows && ncol0 + lc < N)
-                *(uint2 *)(O + (size_t)(mt.row_begin + m) * N + ncol0 + lc) = v;
-        }
-        wave_lds_sync();  // the region is rewritten by the next token tile
     }
+    emit_token_tile<kFirst>(p, c, mt, n0, N, ring, t, s);
 }
 
 template <bool kFirst, int kPhase>
@@ -423,7 +454,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     mt.slot = un.slot; mt.row_begin = un.row_begin; mt.rows = un.rows; mt.single = un.info & 1;
     const int n0 = ((un.info >> 1) + j % spp) * BNO;
 
-    __shared__ __attribute__((aligned(1024))) char ring[kLdsBytes];
+    __shared__ __attribute__((aligned(1024))) char ring[kPhase == 2 ? kWaves * kEpiBytes : kLdsBytes];   // phase 2 only stages its epilogue
     WaveCtx c;
     c.lane = threadIdx.x & 63;
     c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -501,15 +532,19 @@ __global__ __launch_bounds__(kThreads, 1) void k_expert_gemm_mfma8(Pass p)
     }
     // token tiles this wavefront multiplies: wm, wm+2, ... < n_tt.  The whole rest of the
     // wavefront's work is specialised on that count so that its K loop is straight-line code.
-    const int tsel = kPhase == 2 ? (int)blockIdx.y : -1;   // phase 2 is spread over the token tiles too: a workgroup adds up one per wavefront
     const int ntc = (c.n_tt - c.wm + 1) >> 1;
-    switch (ntc) {
-    case 5: wave_body<kFirst, 5, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
-    case 4: wave_body<kFirst, 4, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
-    case 3: wave_body<kFirst, 3, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
-    case 2: wave_body<kFirst, 2, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
-    case 1: wave_body<kFirst, 1, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
-    default: wave_body<kFirst, 0, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part, n_parts, tsel); break;
+    if constexpr (kPhase == 2) {
+        // phase 2 is spread over the token tiles too: a workgroup adds up one per wavefront
+        if ((int)blockIdx.y < ntc) sum_body<kFirst>(p, c, mt, n0, N, ring, tile_sets, n_parts, (int)blockIdx.y);
+    } else {
+        switch (ntc) {
+        case 5: wave_body<kFirst, 5, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        case 4: wave_body<kFirst, 4, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        case 3: wave_body<kFirst, 3, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        case 2: wave_body<kFirst, 2, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        case 1: wave_body<kFirst, 1, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        default: wave_body<kFirst, 0, kPhase>(p, c, mt, n0, N, KT, ring, tile_sets, part); break;
+        }
     }
 }
 
