@@ -365,6 +365,18 @@ def test_configuration_limits():
     _full_check(_case(wl))
 
 
+@pytest.mark.parametrize("n_group,per,topk_group,top_k", [(3, 5, 2, 4), (6, 12, 4, 7), (5, 24, 3, 8), (12, 3, 7, 6)])
+def test_group_counts_and_sizes_that_are_no_powers_of_two(n_group, per, topk_group, top_k):
+    """The selection kernel shares a group's experts out over a power-of-two number of lanes and finds an
+    expert's group by a shift when the group size allows it: group counts and sizes of every other kind take
+    the general path (division, lanes past the last group idle)."""
+    wl = MoEWorkload(name="odd_groups", tokens=210, hidden=192, inter=72, n_experts=n_group * per, top_k=top_k,
+                     n_slots=n_group * per + 1, n_local=n_group * per, act_dtype="bf16", router_dtype="f32",
+                     gate="sigmoid_group", n_group=n_group, topk_group=topk_group, routed_scale=1.5, n_shared=1,
+                     seed=40 + n_group)
+    _full_check(_case(wl))
+
+
 def test_groups_of_one_expert():
     """n_group = E: every group is a single expert and its score is that expert's score alone; keeping the
     topk_group best groups and then the k best experts is plain top-k."""
