@@ -58,7 +58,6 @@ constexpr int kWaves = 8;
 constexpr int kBN = 256;                   // weight rows per workgroup
 constexpr int kMaxTT = 10;                 // token tiles (32 rows) per workgroup
 constexpr int kBM = kMaxTT * 32;           // 320: a whole group with its ragged tail in the usual case
-constexpr int kRows = kBN + kBM;           // LDS rows per stage
 constexpr int kBKW = 64;                   // weight K-step: 128 bytes per row = one whole cache line
 constexpr int kWStage = kBN * kBKW * 2;    // 32 KB of weight rows per weight step
 constexpr int kXStage = kBM * kBK * 2;     // 40 KB of token rows per K-step

@@ -116,7 +116,7 @@ Layout make_layout(const moe_config_t &c)
     L.n_tiles = take(4);
     // unit lists of the large-tile GEMMs (layers they can serve): one entry per (tile, run of N-slices), in rows of 8
     L.unit_cap = 0;
-    if (c.act_dtype == MOE_BF16 && c.hidden % 64 == 0 && c.inter % 64 == 0 && (long long)A >= 48ll * S) {
+    if (c.act_dtype == MOE_BF16 && c.hidden % 64 == 0 && c.inter % 64 == 0 && A >= 48 * S) {
         const size_t big_tiles = (A + mfma8_tile_rows() - 1) / mfma8_tile_rows() + S;
         const int ns0 = mfma8_n_slices(c.hidden, c.inter, 0), ns1 = mfma8_n_slices(c.hidden, c.inter, 1);
         L.unit_cap = 8 * (size_t)mfma8_grid_rows((int)big_tiles, ns0 > ns1 ? ns0 : ns1);
@@ -128,7 +128,7 @@ Layout make_layout(const moe_config_t &c)
     L.y = take(esize(c.act_dtype) * A * c.hidden);
     // partial sums of split tiles: only layers whose large-tile GEMMs can have contractions long enough to split
     L.has_partials = c.act_dtype == MOE_BF16 && c.hidden % 64 == 0 && c.inter % 64 == 0 && (c.hidden >= 4096 || c.inter >= 4096) &&
-                     (long long)A >= 48ll * S;
+                     A >= 48 * S;
     L.partials = take(L.has_partials ? mfma8_partial_bytes() : 0);
     L.total = o;
     return L;
