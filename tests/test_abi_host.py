@@ -7,7 +7,6 @@ import re
 import numpy as np
 import pytest
 
-import paper_2510_02613_amd as M
 from paper_2510_02613_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))

@@ -1,7 +1,6 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same
 seeded inputs.  Integer results (routing, bookkeeping) are bit exact up to flagged score
 near-ties; outputs meet max-relative-error 1e-2 (bf16) / 1e-4 (fp32)."""
-import dataclasses
 
 import numpy as np
 import pytest

@@ -99,7 +99,6 @@ def _check(wl, emap, local):
     inp = make_inputs(wl)
     case = Case.__new__(Case)
     # build the slot pools by hand: Case.place assumes local experts are 0..n_local-1
-    import oracle
     from oracle import LayerSpec
     from paper_2510_02613_amd.layer import MoELayer
     shared_slots = np.arange(wl.n_slots - wl.n_shared, wl.n_slots, dtype=np.int32)

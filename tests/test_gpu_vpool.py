@@ -134,7 +134,7 @@ def test_bound_pools_refuse_slots_without_a_page():
     import torch
     from gpu_util import Case
     from paper_2510_02613_amd import binding as B
-    from paper_2510_02613_amd.layer import VirtualPool, MoELayer
+    from paper_2510_02613_amd.layer import VirtualPool
     wl = MoEWorkload(name="vpool_guard", tokens=300, **MID)
     H, I, S = wl.hidden, wl.inter, wl.n_slots
     p13 = VirtualPool(S, (2 * I, H), torch.int16)

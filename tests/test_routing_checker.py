@@ -2,7 +2,6 @@
 ordering rule allows once fp32 scores closer than 1e-5 count as equal, and nothing else.  Mistakes are
 planted here, on the CPU side, never on the GPU."""
 import numpy as np
-import scipy.special
 
 import oracle
 from oracle import LayerSpec
