@@ -42,8 +42,10 @@
 // and up value r+8 of the same (token, column), so silu(g)*u needs no shuffles.
 //
 // Epilogue: every wavefront transposes its accumulators through a private LDS
-// region (row stride = row bytes + 8, conflict free for the 8-byte writes) and
-// writes whole contiguous row segments, so global stores are full cache lines.
+// region (row stride = row bytes + 16: rows stay 16-byte aligned for the copy out, the
+// 8-byte writes meet two to a bank) and writes whole contiguous row segments, 16 bytes
+// per lane, so global stores are full cache lines.  The epilogue is instruction bound
+// (3 us of a workgroup): 16-byte rather than 8-byte copies out halve its longest loop.
 #include "moe_internal.h"
 
 namespace emoe {
@@ -79,8 +81,8 @@ constexpr int kXcds = 8;
 constexpr int kMaxPartialSets = 256;        // partial-sum sets the workspace has room for: one round of a 256-unit chip
 constexpr int kTC = kMaxTT / 2;            // token tiles per wavefront
 constexpr int kWT = 2;                     // weight tiles per wavefront
-constexpr int kEpiStride1 = 2 * kWT * 16 + 8;   // GEMM-1: 32 h columns per wavefront, bytes per staged row
-constexpr int kEpiStride2 = 2 * kWT * 32 + 8;   // GEMM-2: 64 y columns per wavefront
+constexpr int kEpiStride1 = 2 * kWT * 16 + 16;  // GEMM-1: 32 h columns per wavefront, bytes per staged row (rows stay 16-byte aligned)
+constexpr int kEpiStride2 = 2 * kWT * 32 + 16;  // GEMM-2: 64 y columns per wavefront
 constexpr int kEpiBytes = 32 * kEpiStride2;     // one token tile of one wavefront
 constexpr int kLdsBytes = kRingBytes;
 static_assert(kWaves * kEpiBytes <= kRingBytes, "epilogue staging reuses the ring");
@@ -284,11 +286,12 @@ __device__ __forceinline__ void emit_token_tile(const Pass &p, const WaveCtx &c,
     constexpr int STRIDE = kFirst ? kEpiStride1 : kEpiStride2;
     char *mine = ring + c.wave * kEpiBytes;
     const int l31 = c.lane & 31, khalf = c.lane >> 5;
-    constexpr int LPR = COLS / 4;                           // copy out: 8 bytes per lane, LPR lanes per row,
+    constexpr int LPR = COLS / 8;                           // copy out: 16 bytes per lane, LPR lanes per row,
     constexpr int RPI = 64 / LPR;                           // 64/LPR rows per instruction
+    static_assert(STRIDE % 16 == 0 && kEpiBytes % 16 == 0 && 32 % RPI == 0, "16-byte reads of the staged rows");
     uint16_t *O = (uint16_t *)(kFirst ? p.h : p.y);
     const int ncol0 = n0 + c.wn * COLS;
-    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 4;
+    const int lr = c.lane / LPR, lc = (c.lane % LPR) * 8;
     char *row = mine + l31 * STRIDE;
 #pragma unroll
     for (int a = 0; a < kWT; ++a) {
@@ -314,9 +317,9 @@ __device__ __forceinline__ void emit_token_tile(const Pass &p, const WaveCtx &c,
     for (int r0 = 0; r0 < 32; r0 += RPI) {
         const int rr = r0 + lr;                       // row inside the token tile
         const int m = (2 * t + c.wm) * 32 + rr;       // row inside the chunk
-        const uint2 w = *(const uint2 *)(mine + rr * STRIDE + lc * 2);
-        if (m < mt.rows && ncol0 + lc < N)
-            *(uint2 *)(O + (size_t)(mt.row_begin + m) * N + ncol0 + lc) = w;
+        const uint4 w = *(const uint4 *)(mine + rr * STRIDE + lc * 2);
+        if (m < mt.rows && ncol0 + lc < N)   // N is a multiple of 64: the lane's 8 columns exist together
+            *(uint4 *)(O + (size_t)(mt.row_begin + m) * N + ncol0 + lc) = w;
     }
     wave_lds_sync();  // the region is rewritten by the next token tile
 }
