@@ -606,7 +606,7 @@ def cpu_baseline(wl, inp, w13_pool, w2_pool, expert_map, shared, target_s):
         return time.perf_counter() - t0
 
     threads = oracle.max_threads()
-    n0 = min(wl.tokens, 2 * threads)
+    n0 = min(wl.tokens, 8 * threads)   # a probe of two tokens per thread overestimates the time per token by half
     t_probe = run(n0)
     n = int(max(n0, min(wl.tokens, n0 * target_s / max(t_probe, 1e-3))))
     n = max(threads, n // threads * threads) if n < wl.tokens else wl.tokens
